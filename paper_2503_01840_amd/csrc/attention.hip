@@ -1,0 +1,308 @@
+// Tree-masked attention against a (ragged) KV cache.
+//
+// Every query row sees the first n_prefix slots of its sequence unconditionally and the following
+// n_tail slots (tree nodes / draft rows, just written to the cache) according to a 128-bit mask that
+// was derived from the parent array: no dense rows x keys mask exists anywhere.
+//
+// bf16 kernel (head_dim 128): flash-style, split over the key range.
+//   * workgroup = (sequence, KV head, block of 128 query rows of that KV head's group, key split);
+//     the rows of one KV head's group are (query head in group, node) pairs, so all of them share
+//     the K/V tiles staged in LDS;
+//   * each wavefront owns 32 query rows.  Scores are produced transposed, S^T = K Q^T, with
+//     v_mfma_f32_32x32x16_bf16, so a lane holds 16 keys of ONE query: the running max / sum need a
+//     single cross-lane exchange and exp(S^T) is already in B-operand position for O^T += V^T P^T;
+//   * V tiles are transposed on their way into LDS (keys permuted to match that operand order);
+//   * partial (max, sum, O) per split go to scratch; a second kernel merges the splits and writes the
+//     result in the fragment-major layout the output projection reads.
+// fp32 kernel: one workgroup per (row, head), scores in LDS; exact arithmetic for the tiny model.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+constexpr int D = 128;
+constexpr int KT = 32;                       // keys per tile
+constexpr int KROW = D * 2 + 16;             // LDS bytes per staged key row
+constexpr int VROW = KT * 2 + 16;            // LDS bytes per transposed value row (one head-dim index)
+constexpr int TILE_BYTES = KT * KROW + D * VROW;
+constexpr float NEG = -1e30f;
+
+struct AttnParams {
+  const bf16_t* q;
+  const bf16_t* kc;
+  const bf16_t* vc;
+  const SeqInfo* seq;
+  const uint32_t* mask;
+  int B, N, H, Hkv, n_splits, n_qblocks;
+  float scale_log2;
+  float* o_part;     // [B][H][n_splits][N][D]
+  float* ml_part;    // [B][H][n_splits][N][2]
+};
+
+__global__ __launch_bounds__(256, 2) void attn_tree_bf16_kernel(AttnParams p) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * TILE_BYTES];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int idx = blockIdx.x;
+  const int g = idx % p.Hkv; idx /= p.Hkv;
+  const int split = idx % p.n_splits; idx /= p.n_splits;
+  const int qb = idx % p.n_qblocks;
+  const int b = idx / p.n_qblocks;
+  const int G = p.H / p.Hkv, N = p.N;
+  const SeqInfo si = p.seq[b];
+  const int L = si.n_prefix + si.n_tail;
+
+  // this lane's query: row rho of the KV head's group
+  const int rho = qb * 128 + wave * 32 + (lane & 31);
+  const bool q_valid = rho < G * N;
+  const int head = g * G + (q_valid ? rho / N : 0), node = q_valid ? rho % N : 0;
+  const int row = b * N + node;
+  const bool wave_active = qb * 128 + wave * 32 < G * N;
+  const int kg = lane >> 5;
+
+  u32x4 qf[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    if (q_valid) qf[ks] = *(const u32x4*)(p.q + ((size_t)row * p.H + head) * D + ks * 16 + kg * 8);
+    else qf[ks] = (u32x4){0u, 0u, 0u, 0u};
+  }
+  uint32_t mw[4];
+#pragma unroll
+  for (int w = 0; w < 4; ++w) mw[w] = p.mask[(size_t)row * 4 + w];
+
+  const int n_tiles = (L + KT - 1) / KT;
+  const int tps = (n_tiles + p.n_splits - 1) / p.n_splits;
+  const int t_begin = split * tps, t_end = min(n_tiles, t_begin + tps);
+
+  // staging roles: K chunks c = tid, tid+256 (key = c>>4, 16-byte column = c&15);
+  // V: head-dim chunk vc8 = tid&15, key pair vp = tid>>4 at permuted positions 2vp, 2vp+1
+  const int vc8 = tid & 15, vp = tid >> 4;
+  int vkey[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int pi = 2 * vp + u;
+    vkey[u] = 16 * (pi >> 4) + 8 * ((pi >> 2) & 1) + 4 * ((pi >> 3) & 1) + (pi & 3);
+  }
+  u32x4 kreg[2], vreg[2];
+  auto load_tile = [&](int t) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int c = tid + 256 * i;
+      const int kk = min(t * KT + (c >> 4), L - 1);
+      kreg[i] = *(const u32x4*)(p.kc + ((size_t)(si.kv_base + kk) * p.Hkv + g) * D + (c & 15) * 8);
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int kk = min(t * KT + vkey[u], L - 1);
+      vreg[u] = *(const u32x4*)(p.vc + ((size_t)(si.kv_base + kk) * p.Hkv + g) * D + vc8 * 8);
+    }
+  };
+  auto store_tile = [&](unsigned char* buf) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int c = tid + 256 * i;
+      *(u32x4*)(buf + (c >> 4) * KROW + (c & 15) * 16) = kreg[i];
+    }
+    unsigned char* vt = buf + KT * KROW;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t a = vreg[0][j], c2 = vreg[1][j];
+      *(uint32_t*)(vt + (vc8 * 8 + 2 * j) * VROW + 4 * vp) = (a & 0xFFFFu) | (c2 << 16);
+      *(uint32_t*)(vt + (vc8 * 8 + 2 * j + 1) * VROW + 4 * vp) = (a >> 16) | (c2 & 0xFFFF0000u);
+    }
+  };
+
+  floatx16 o[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+  float m_run = NEG, l_run = 0.f;
+
+  if (t_begin < t_end) load_tile(t_begin);
+  for (int t = t_begin; t < t_end; ++t) {
+    unsigned char* buf = smem + ((t - t_begin) & 1) * TILE_BYTES;
+    store_tile(buf);
+    if (t + 1 < t_end) load_tile(t + 1);
+    __syncthreads();
+    if (!wave_active) continue;
+    floatx16 s;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const u32x4 a = *(const u32x4*)(buf + (lane & 31) * KROW + (ks * 16 + kg * 8) * 2);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, qf[ks]), s, 0,
+                                                   0, 0);
+    }
+    const int k0 = t * KT;
+    const bool need_mask = k0 + KT > si.n_prefix;       // tile touches the masked tail or runs past the end
+    float mx = NEG;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float v = s[r] * p.scale_log2;
+      if (need_mask) {
+        const int kk = k0 + 8 * (r >> 2) + 4 * kg + (r & 3);
+        const int off = kk - si.n_prefix;
+        bool vis = kk < L;
+        if (vis && off >= 0) vis = (mw[(off >> 5) & 3] >> (off & 31)) & 1u;
+        v = vis ? v : NEG;
+      }
+      s[r] = v;
+      mx = fmaxf(mx, v);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = exp2f(m_run - m_new);
+    float ls = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      s[r] = exp2f(s[r] - m_new);
+      ls += s[r];
+    }
+    ls += __shfl_xor(ls, 32, 64);
+    l_run = l_run * alpha + ls;
+    m_run = m_new;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+    }
+    // P^T as two B operands: operand m holds keys 16m + {4kg..4kg+3, 8+4kg..8+4kg+3} = registers 8m..8m+7
+    u32x4 pf[2];
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        pf[m][j] = (uint32_t)f32_to_bf16(s[8 * m + 2 * j]) | ((uint32_t)f32_to_bf16(s[8 * m + 2 * j + 1]) << 16);
+    const unsigned char* vt = buf + KT * KROW;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int m = 0; m < 2; ++m) {
+        const u32x4 a = *(const u32x4*)(vt + (db * 32 + (lane & 31)) * VROW + (m * 16 + kg * 8) * 2);
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, pf[m]),
+                                                       o[db], 0, 0, 0);
+      }
+  }
+
+  if (q_valid) {
+    const size_t pr = (((size_t)b * p.H + head) * p.n_splits + split) * N + node;
+    float* op = p.o_part + pr * D;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) {
+        floatx4 v = {o[db][4 * gq], o[db][4 * gq + 1], o[db][4 * gq + 2], o[db][4 * gq + 3]};
+        *(floatx4*)(op + db * 32 + 8 * gq + 4 * kg) = v;
+      }
+    if (kg == 0) {
+      p.ml_part[pr * 2] = m_run;
+      p.ml_part[pr * 2 + 1] = l_run;
+    }
+  }
+}
+
+__global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict__ o_part, const float* __restrict__ ml_part,
+                                                        int N, int H, int n_splits, bf16_t* __restrict__ out) {
+  const int h = blockIdx.x % H, r = blockIdx.x / H, b = r / N, node = r % N, d = threadIdx.x;
+  const size_t base = (((size_t)b * H + h) * n_splits) * N + node;
+  float M = NEG;
+  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ml_part[(base + (size_t)s * N) * 2]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    const size_t pr = base + (size_t)s * N;
+    const float w = exp2f(ml_part[pr * 2] - M);
+    num += w * o_part[pr * D + d];
+    den += w * ml_part[pr * 2 + 1];
+  }
+  out[xf_offset(r, h * D + d, H * D)] = f32_to_bf16(num / den);
+}
+
+// ---------------------------------------------------------------------------------------------- fp32
+__global__ __launch_bounds__(256) void attn_tree_f32_kernel(const float* __restrict__ q, const float* __restrict__ kc,
+                                                           const float* __restrict__ vc, const SeqInfo* __restrict__ seq,
+                                                           const uint32_t* __restrict__ mask, int N, int H, int Hkv, int d,
+                                                           float scale, float* __restrict__ out) {
+  extern __shared__ float sc[];
+  __shared__ float red[17];
+  const int r = blockIdx.x, h = blockIdx.y, b = r / N, g = h * Hkv / H, tid = threadIdx.x;
+  const SeqInfo si = seq[b];
+  const int L = si.n_prefix + si.n_tail;
+  const float* qr = q + ((size_t)r * H + h) * d;
+  float mx = -INFINITY;
+  for (int kk = tid; kk < L; kk += 256) {
+    const int off = kk - si.n_prefix;
+    bool vis = true;
+    if (off >= 0) vis = (mask[(size_t)r * 4 + ((off >> 5) & 3)] >> (off & 31)) & 1u;
+    float s = -INFINITY;
+    if (vis) {
+      const float* kr = kc + ((size_t)(si.kv_base + kk) * Hkv + g) * d;
+      float acc = 0.f;
+      for (int i = 0; i < d; ++i) acc = fmaf(qr[i], kr[i], acc);
+      s = acc * scale;
+    }
+    sc[kk] = s;
+    mx = fmaxf(mx, s);
+  }
+  mx = block_max(mx, red);
+  float sum = 0.f;
+  for (int kk = tid; kk < L; kk += 256) {
+    const float e = expf(sc[kk] - mx);      // exp(-inf) = 0 for masked slots
+    sc[kk] = e;
+    sum += e;
+  }
+  sum = block_sum(sum, red);
+  for (int i = tid; i < d; i += 256) {
+    float acc = 0.f;
+    for (int kk = 0; kk < L; ++kk) acc = fmaf(sc[kk], vc[((size_t)(si.kv_base + kk) * Hkv + g) * d + i], acc);
+    out[(size_t)r * H * d + h * d + i] = acc / sum;
+  }
+}
+
+}  // namespace
+
+int attention_pick_splits(int B, int rows_per_seq, int H, int Hkv, int max_len) {
+  const int G = H / Hkv;
+  const int qblocks = (G * rows_per_seq + 127) / 128;
+  const int base = B * Hkv * qblocks;
+  const int tiles = (max_len + KT - 1) / KT;
+  int s = (512 + base - 1) / base;               // aim at ~2 workgroups per CU
+  s = s < 1 ? 1 : s;
+  const int cap = (tiles + 3) / 4;               // at least 4 key tiles per split
+  if (s > cap) s = cap < 1 ? 1 : cap;
+  return s;
+}
+
+size_t attention_scratch_floats(int R, int H, int d, int max_splits) {
+  return (size_t)R * H * max_splits * (d + 2);
+}
+
+hipError_t launch_tree_attention(bool bf16, const void* q, const void* kcache, const void* vcache, const SeqInfo* seq,
+                                 const uint32_t* mask, int B, int rows_per_seq, int H, int Hkv, int d, int max_len,
+                                 int n_splits, float* scratch, void* out, hipStream_t st) {
+  const int R = B * rows_per_seq;
+  if (!bf16) {
+    const size_t lds = (size_t)max_len * sizeof(float);
+    if (lds > 60 * 1024) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(attn_tree_f32_kernel, dim3(R, H), dim3(256), lds, st, (const float*)q, (const float*)kcache,
+                       (const float*)vcache, seq, mask, rows_per_seq, H, Hkv, d, 1.0f / sqrtf((float)d), (float*)out);
+    return hipGetLastError();
+  }
+  if (d != D || H % Hkv) return hipErrorInvalidValue;
+  AttnParams p;
+  p.q = (const bf16_t*)q; p.kc = (const bf16_t*)kcache; p.vc = (const bf16_t*)vcache;
+  p.seq = seq; p.mask = mask;
+  p.B = B; p.N = rows_per_seq; p.H = H; p.Hkv = Hkv; p.n_splits = n_splits;
+  p.n_qblocks = (H / Hkv * rows_per_seq + 127) / 128;
+  p.scale_log2 = 1.4426950408889634f / sqrtf((float)d);
+  p.o_part = scratch;
+  p.ml_part = scratch + (size_t)R * H * n_splits * D;
+  hipLaunchKernelGGL(attn_tree_bf16_kernel, dim3(B * p.n_qblocks * n_splits * Hkv), dim3(256), 0, st, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(attn_merge_kernel, dim3(R * H), dim3(128), 0, st, p.o_part, p.ml_part, rows_per_seq, H, n_splits,
+                     (bf16_t*)out);
+  return hipGetLastError();
+}

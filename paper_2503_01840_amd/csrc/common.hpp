@@ -1,0 +1,90 @@
+// Shared device helpers for the gfx950 kernels: bf16 conversion, the fragment-major activation
+// layout read by the MFMA GEMMs, and small reductions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint16_t bf16_t;          // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round-to-nearest-even fp32 -> bf16 (inputs are finite in this library)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float load_f32(const T* p, size_t i);
+template <> __device__ __forceinline__ float load_f32<float>(const float* p, size_t i) { return p[i]; }
+template <> __device__ __forceinline__ float load_f32<bf16_t>(const bf16_t* p, size_t i) { return bf16_to_f32(p[i]); }
+
+template <typename T> __device__ __forceinline__ void store_from_f32(T* p, size_t i, float v);
+template <> __device__ __forceinline__ void store_from_f32<float>(float* p, size_t i, float v) { p[i] = v; }
+template <> __device__ __forceinline__ void store_from_f32<bf16_t>(bf16_t* p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+
+// Fragment-major layout of a bf16 activation matrix X[rows, K] (K % 16 == 0), as the MFMA GEMMs read it:
+// rows are grouped in tiles of 64, K in steps of 16; the 32 rows x 16 k of one (tile, k-step, half)
+// form one 1 KiB block holding, for lane l of a wavefront, the 8 values X[32*half + l%32][16*step + 8*(l/32) .. +7]
+// at element offset 8*l.  One such block is exactly the A operand of v_mfma_f32_32x32x16_bf16.
+__host__ __device__ __forceinline__ size_t xf_offset(int row, int k, int K) {
+  const int tile = row >> 6, half = (row >> 5) & 1, r = row & 31;
+  const int step = k >> 4, kg = (k >> 3) & 1, e = k & 7;
+  return ((((size_t)tile * (K >> 4) + step) * 2 + half) * 64 + (r + 32 * kg)) * 8 + e;
+}
+__host__ __device__ __forceinline__ size_t xf_elems(int rows, int K) { return (size_t)((rows + 63) / 64) * 64 * K; }
+
+// Activation store policy: BF16 path writes fragment-major bf16, FP32 path writes row-major fp32.
+template <bool BF16> struct Act;
+template <> struct Act<true> {
+  typedef bf16_t type;
+  static __device__ __forceinline__ void store(bf16_t* p, int row, int k, int K, float v) { p[xf_offset(row, k, K)] = f32_to_bf16(v); }
+};
+template <> struct Act<false> {
+  typedef float type;
+  static __device__ __forceinline__ void store(float* p, int row, int k, int K, float v) { p[(size_t)row * K + k] = v; }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Block-wide sum for blockDim.x a multiple of 64, <= 1024.  `red` is a __shared__ float[17].
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float s = 0.f;
+    for (int i = 0; i < nw; ++i) s += red[i];
+    red[16] = s;
+  }
+  __syncthreads();
+  return red[16];
+}
+__device__ __forceinline__ float block_max(float v, float* red) {
+  v = wave_max(v);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float s = red[0];
+    for (int i = 1; i < nw; ++i) s = fmaxf(s, red[i]);
+    red[16] = s;
+  }
+  __syncthreads();
+  return red[16];
+}

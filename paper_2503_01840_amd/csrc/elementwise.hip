@@ -1,0 +1,287 @@
+// Row-wise kernels between the GEMMs: embedding gather, residual add + RMSNorm, rotary embedding and
+// cache write, tree bookkeeping, SwiGLU (fp32 path), feature packing.  All are tiny next to the weight
+// streams; they exist to hand the next GEMM its operand in the layout it reads.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace {
+
+template <typename TW>
+__global__ __launch_bounds__(256) void embed_rows_kernel(const TW* __restrict__ embed, const int32_t* __restrict__ tok,
+                                                        int k, int vocab, float* __restrict__ x) {
+  const int r = blockIdx.x;
+  const int t = min(max(tok[r], 0), vocab - 1);
+  for (int c = threadIdx.x; c < k; c += 256) x[(size_t)r * k + c] = load_f32(embed, (size_t)t * k + c);
+}
+
+struct CopyOut { float* p[4]; };
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void add_norm_kernel(float* __restrict__ x, const float* __restrict__ partial, int S,
+                                                      int R, int k, const typename Act<BF16>::type* __restrict__ gain,
+                                                      float eps, typename Act<BF16>::type* __restrict__ act, CopyOut co) {
+  __shared__ float red[17];
+  const int r = blockIdx.x;
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < k; c += 256) {
+    float v = x[(size_t)r * k + c];
+    for (int s = 0; s < S; ++s) v += partial[((size_t)s * R + r) * k + c];
+    x[(size_t)r * k + c] = v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (co.p[i]) co.p[i][(size_t)r * k + c] = v;
+    ss += v * v;
+  }
+  ss = block_sum(ss, red);
+  if (act == nullptr) return;
+  const float inv = 1.0f / sqrtf(ss / (float)k + eps);
+  for (int c = threadIdx.x; c < k; c += 256)
+    Act<BF16>::store(act, r, c, k, x[(size_t)r * k + c] * inv * load_f32(gain, c));
+}
+
+// cos/sin of pos * theta^(-2i/d) in fp64, stored fp32: cs[r][i] = cos, cs[r][d/2 + i] = sin
+__device__ __forceinline__ void rope_entry(float* cs, int r, int i, int d, int pos, float theta) {
+  const double inv = pow((double)theta, -2.0 * (double)i / (double)d);
+  double s, c;
+  sincos((double)pos * inv, &s, &c);
+  cs[(size_t)r * d + i] = (float)c;
+  cs[(size_t)r * d + d / 2 + i] = (float)s;
+}
+
+__global__ __launch_bounds__(256) void tree_prep_kernel(const int32_t* __restrict__ parent,
+                                                       const int32_t* __restrict__ kv_indptr,
+                                                       const int32_t* __restrict__ prefix_len, int N, int d, float theta,
+                                                       int32_t* __restrict__ depth, uint32_t* __restrict__ mask,
+                                                       int32_t* __restrict__ slot, float* __restrict__ cs,
+                                                       SeqInfo* __restrict__ seq) {
+  __shared__ int sdepth[64];
+  const int b = blockIdx.x, i = threadIdx.x;
+  const int P = prefix_len[b], base = kv_indptr[b];
+  if (i < N) {
+    uint32_t m[4] = {0u, 0u, 0u, 0u};
+    int cur = i, dep = 0;
+    for (int it = 0; it < N; ++it) {                     // bounded walk: malformed parents cannot loop
+      m[cur >> 5] |= 1u << (cur & 31);
+      const int p = parent[b * N + cur];
+      if (p < 0 || p >= cur) break;
+      cur = p;
+      ++dep;
+    }
+    sdepth[i] = dep;
+    const int r = b * N + i;
+    depth[r] = dep;
+    slot[r] = base + P + i;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) mask[r * 4 + w] = m[w];
+  }
+  if (i == 0) { seq[b].kv_base = base; seq[b].n_prefix = P; seq[b].n_tail = N; seq[b].pad = 0; }
+  __syncthreads();
+  const int half = d / 2;
+  for (int e = i; e < N * half; e += 256) {
+    const int row = e / half, f = e % half;
+    rope_entry(cs, b * N + row, f, d, P + sdepth[row], theta);
+  }
+}
+
+__global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restrict__ pos, int R, int d, float theta,
+                                                        float* __restrict__ cs) {
+  const int half = d / 2;
+  for (int e = blockIdx.x * 256 + threadIdx.x; e < R * half; e += gridDim.x * 256) rope_entry(cs, e / half, e % half, d, pos[e / half], theta);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void rope_kv_write_kernel(const float* __restrict__ qkv, int S, int R, int H, int Hkv,
+                                                           int d, const float* __restrict__ cs,
+                                                           const int32_t* __restrict__ slot,
+                                                           typename Act<BF16>::type* __restrict__ q,
+                                                           typename Act<BF16>::type* __restrict__ kc,
+                                                           typename Act<BF16>::type* __restrict__ vc) {
+  typedef typename Act<BF16>::type T;
+  const int r = blockIdx.x, half = d / 2, NT = (H + 2 * Hkv) * d;
+  const size_t sl = (size_t)slot[r];
+  for (int e = threadIdx.x; e < (H + 2 * Hkv) * half; e += 256) {
+    const int h = e / half, i = e % half;
+    float x1 = 0.f, x2 = 0.f;
+    for (int s = 0; s < S; ++s) {
+      const float* row = qkv + ((size_t)s * R + r) * NT + h * d;
+      x1 += row[i];
+      x2 += row[i + half];
+    }
+    if (h < H + Hkv) {
+      const float c = cs[(size_t)r * d + i], sn = cs[(size_t)r * d + half + i];
+      const float o1 = x1 * c - x2 * sn, o2 = x2 * c + x1 * sn;
+      T* dst = h < H ? q + ((size_t)r * H + h) * d : kc + (sl * Hkv + (h - H)) * d;
+      store_from_f32(dst, i, o1);
+      store_from_f32(dst, i + half, o2);
+    } else {
+      T* dst = vc + (sl * Hkv + (h - H - Hkv)) * d;
+      store_from_f32(dst, i, x1);
+      store_from_f32(dst, i + half, x2);
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void swiglu_f32_kernel(const float* __restrict__ gu, int I, float* __restrict__ h) {
+  const int r = blockIdx.x;
+  for (int c = threadIdx.x; c < I; c += 256) {
+    const float g = gu[(size_t)r * 2 * I + c], u = gu[(size_t)r * 2 * I + I + c];
+    h[(size_t)r * I + c] = g / (1.f + expf(-g)) * u;
+  }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void pack3_kernel(const float* __restrict__ a, const float* __restrict__ b,
+                                                   const float* __restrict__ c, int k,
+                                                   typename Act<BF16>::type* __restrict__ act) {
+  const int r = blockIdx.x;
+  for (int j = threadIdx.x; j < k; j += 256) {
+    Act<BF16>::store(act, r, j, 3 * k, a[(size_t)r * k + j]);
+    Act<BF16>::store(act, r, k + j, 3 * k, b[(size_t)r * k + j]);
+    Act<BF16>::store(act, r, 2 * k + j, 3 * k, c[(size_t)r * k + j]);
+  }
+}
+
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int S, size_t MN,
+                                                             float* __restrict__ out) {
+  for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < MN; e += (size_t)gridDim.x * 256) {
+    float v = 0.f;
+    for (int s = 0; s < S; ++s) v += partial[(size_t)s * MN + e];
+    out[e] = v;
+  }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void draft_input_kernel(const typename Act<BF16>::type* __restrict__ embed, int vocab,
+                                                         const int32_t* __restrict__ tok, const float* __restrict__ feat,
+                                                         const int32_t* __restrict__ src_row, int k,
+                                                         const typename Act<BF16>::type* __restrict__ g_embed,
+                                                         const typename Act<BF16>::type* __restrict__ g_feat, float eps,
+                                                         typename Act<BF16>::type* __restrict__ act,
+                                                         float* __restrict__ y) {
+  __shared__ float red[17];
+  const int r = blockIdx.x;
+  const int t = min(max(tok[r], 0), vocab - 1);
+  const float* f = feat + (size_t)(src_row ? src_row[r] : r) * k;
+  float se = 0.f, sf = 0.f;
+  for (int c = threadIdx.x; c < k; c += 256) {
+    const float e = load_f32(embed, (size_t)t * k + c), v = f[c];
+    y[(size_t)r * k + c] = v;
+    se += e * e;
+    sf += v * v;
+  }
+  se = block_sum(se, red);
+  sf = block_sum(sf, red);
+  const float ie = 1.0f / sqrtf(se / (float)k + eps), iv = 1.0f / sqrtf(sf / (float)k + eps);
+  for (int c = threadIdx.x; c < k; c += 256) {
+    Act<BF16>::store(act, r, c, 2 * k, load_f32(embed, (size_t)t * k + c) * ie * load_f32(g_embed, c));
+    Act<BF16>::store(act, r, k + c, 2 * k, f[c] * iv * load_f32(g_feat, c));
+  }
+}
+
+__global__ __launch_bounds__(64) void draft_prep1_kernel(const int32_t* __restrict__ kv_indptr,
+                                                        const int32_t* __restrict__ prefix_len, int n_new,
+                                                        int32_t* __restrict__ pos, int32_t* __restrict__ slot,
+                                                        uint32_t* __restrict__ mask, SeqInfo* __restrict__ seq) {
+  const int j = threadIdx.x, P = prefix_len[0], base = kv_indptr[0];
+  if (j < n_new) {
+    pos[j] = P + j;
+    slot[j] = base + P + j;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {                        // causal among the new rows: bits 0..j
+      const int lo = 32 * w;
+      mask[j * 4 + w] = j < lo ? 0u : (j - lo >= 31 ? 0xFFFFFFFFu : ((2u << (j - lo)) - 1u));
+    }
+  }
+  if (j == 0) { seq[0].kv_base = base; seq[0].n_prefix = P; seq[0].n_tail = n_new; seq[0].pad = 0; }
+}
+
+}  // namespace
+
+#define DISPATCH_BF16(flag, KERNEL, grid, block, st, ...)                                       \
+  do {                                                                                          \
+    if (flag) hipLaunchKernelGGL(KERNEL<true>, grid, block, 0, st, __VA_ARGS__);               \
+    else hipLaunchKernelGGL(KERNEL<false>, grid, block, 0, st, __VA_ARGS__);                   \
+  } while (0)
+
+hipError_t launch_embed_rows(bool bf16, const void* embed, const int32_t* tok, int R, int k, int vocab, float* x,
+                             hipStream_t st) {
+  if (bf16) hipLaunchKernelGGL(embed_rows_kernel<bf16_t>, dim3(R), dim3(256), 0, st, (const bf16_t*)embed, tok, k, vocab, x);
+  else hipLaunchKernelGGL(embed_rows_kernel<float>, dim3(R), dim3(256), 0, st, (const float*)embed, tok, k, vocab, x);
+  return hipGetLastError();
+}
+
+hipError_t launch_add_norm(bool bf16, float* x, const float* partial, int S, int R, int k, const void* gain, float eps,
+                           void* act, float* const copy_out[4], hipStream_t st) {
+  CopyOut co;
+  for (int i = 0; i < 4; ++i) co.p[i] = copy_out ? copy_out[i] : nullptr;
+  if (bf16)
+    hipLaunchKernelGGL(add_norm_kernel<true>, dim3(R), dim3(256), 0, st, x, partial, S, R, k, (const bf16_t*)gain, eps,
+                       (bf16_t*)act, co);
+  else
+    hipLaunchKernelGGL(add_norm_kernel<false>, dim3(R), dim3(256), 0, st, x, partial, S, R, k, (const float*)gain, eps,
+                       (float*)act, co);
+  return hipGetLastError();
+}
+
+hipError_t launch_tree_prep(const int32_t* parent, const int32_t* kv_indptr, const int32_t* prefix_len, int B, int N,
+                            int head_dim, float theta, int32_t* depth, uint32_t* mask, int32_t* slot, float* cs,
+                            SeqInfo* seq, hipStream_t st) {
+  if (N > 64) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(tree_prep_kernel, dim3(B), dim3(256), 0, st, parent, kv_indptr, prefix_len, N, head_dim, theta, depth,
+                     mask, slot, cs, seq);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_table(const int32_t* pos, int R, int head_dim, float theta, float* cs, hipStream_t st) {
+  const int blocks = (R * head_dim / 2 + 255) / 256;
+  hipLaunchKernelGGL(rope_table_kernel, dim3(blocks), dim3(256), 0, st, pos, R, head_dim, theta, cs);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_kv_write(bool bf16, const float* qkv_partial, int S, int R, int H, int Hkv, int d, const float* cs,
+                                const int32_t* slot, void* q, void* kcache, void* vcache, hipStream_t st) {
+  if (bf16)
+    hipLaunchKernelGGL(rope_kv_write_kernel<true>, dim3(R), dim3(256), 0, st, qkv_partial, S, R, H, Hkv, d, cs, slot,
+                       (bf16_t*)q, (bf16_t*)kcache, (bf16_t*)vcache);
+  else
+    hipLaunchKernelGGL(rope_kv_write_kernel<false>, dim3(R), dim3(256), 0, st, qkv_partial, S, R, H, Hkv, d, cs, slot,
+                       (float*)q, (float*)kcache, (float*)vcache);
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu_f32(const float* gu, int R, int I, float* h, hipStream_t st) {
+  hipLaunchKernelGGL(swiglu_f32_kernel, dim3(R), dim3(256), 0, st, gu, I, h);
+  return hipGetLastError();
+}
+
+hipError_t launch_pack3(bool bf16, const float* a, const float* b, const float* c, int M, int k, void* act, hipStream_t st) {
+  if (bf16) hipLaunchKernelGGL(pack3_kernel<true>, dim3(M), dim3(256), 0, st, a, b, c, k, (bf16_t*)act);
+  else hipLaunchKernelGGL(pack3_kernel<false>, dim3(M), dim3(256), 0, st, a, b, c, k, (float*)act);
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce_partials(const float* partial, int S, int M, int N, float* out, hipStream_t st) {
+  const size_t MN = (size_t)M * N;
+  const int blocks = (int)((MN + 255) / 256 < 1024 ? (MN + 255) / 256 : 1024);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks), dim3(256), 0, st, partial, S, MN, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_draft_input(bool bf16, const void* embed, int vocab, const int32_t* tok, const float* feat,
+                              const int32_t* src_row, int M, int k, const void* g_embed, const void* g_feat, float eps,
+                              void* act, float* y, hipStream_t st) {
+  if (bf16)
+    hipLaunchKernelGGL(draft_input_kernel<true>, dim3(M), dim3(256), 0, st, (const bf16_t*)embed, vocab, tok, feat, src_row,
+                       k, (const bf16_t*)g_embed, (const bf16_t*)g_feat, eps, (bf16_t*)act, y);
+  else
+    hipLaunchKernelGGL(draft_input_kernel<false>, dim3(M), dim3(256), 0, st, (const float*)embed, vocab, tok, feat, src_row,
+                       k, (const float*)g_embed, (const float*)g_feat, eps, (float*)act, y);
+  return hipGetLastError();
+}
+
+hipError_t launch_draft_prep1(const int32_t* kv_indptr, const int32_t* prefix_len, int n_new, int32_t* pos, int32_t* slot,
+                              uint32_t* mask, SeqInfo* seq, hipStream_t st) {
+  if (n_new > 64) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(draft_prep1_kernel, dim3(1), dim3(64), 0, st, kv_indptr, prefix_len, n_new, pos, slot, mask, seq);
+  return hipGetLastError();
+}

@@ -1,0 +1,191 @@
+// Weight-streaming bf16 GEMM for few activation rows:  Y[M, N] = X[M, K] * W[N, K]^T, fp32 accumulate.
+//
+// Every projection of the speculative step (fusion FC, q/k/v, o, gate/up, down, both LM heads) has at
+// most a few dozen rows per sequence, so the kernel is bound by reading W once from HBM.  Design:
+//   * one workgroup (4 wavefronts) owns 64 weight rows and one K range (split-K over blockIdx.y);
+//   * W is read with 16-byte loads that are contiguous per row (16 lanes = 256 B of one row), staged
+//     through registers into a double-buffered, row-padded LDS tile, and read back as MFMA B operands;
+//   * X arrives in the fragment-major layout (one 1 KiB block per MFMA A operand), so it is read straight
+//     from L2 with perfectly coalesced 16-byte loads and never touches LDS;
+//   * the four wavefronts split the K range of a stage (intra-workgroup split-K), each accumulating the
+//     whole 64 x 64 tile with v_mfma_f32_32x32x16_bf16; partial tiles are summed through LDS at the end;
+//   * PF stages of global loads are kept in flight per wavefront (register prefetch ring).
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace {
+
+constexpr int BK = 128;                 // k per stage
+constexpr int BN = 64;                  // weight rows per workgroup
+constexpr int WROW = BK * 2 + 16;       // LDS bytes per staged weight row (padded)
+constexpr int PF = 4;                   // stages in flight
+constexpr int RED_LD = 65;              // floats per row of the reduction buffer
+constexpr int SMEM_BYTES = 4 * 64 * RED_LD * 4;   // >= 2 * BN * WROW
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct GemmParams {
+  const bf16_t* x;
+  const bf16_t* w[3];
+  int rows[3];
+  int nmat, mode;
+  int M, N, K, S, epi;
+  float* out_f32;
+  bf16_t* out_xf;
+};
+
+__device__ __forceinline__ const bf16_t* weight_row(const GemmParams& p, int tile, int row) {
+  if (p.mode == 1) {                                   // 32 gate rows | 32 up rows
+    int r = tile * 32 + (row & 31);
+    r = min(r, p.rows[0] - 1);
+    return p.w[row >> 5] + (size_t)r * p.K;
+  }
+  int n = min(tile * BN + row, p.N - 1);
+  int m = 0;
+  while (m + 1 < p.nmat && n >= p.rows[m]) { n -= p.rows[m]; ++m; }
+  return p.w[m] + (size_t)n * p.K;
+}
+
+template <int MH>
+__global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(GemmParams p) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tile = blockIdx.x, split = blockIdx.y, mtile = blockIdx.z;
+  const int Kc = p.K / p.S, k_begin = split * Kc, KT = Kc / BK;
+
+  const bf16_t* wptr[4];
+  int wlds[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = tid + 256 * i, row = c >> 4, col = c & 15;
+    wptr[i] = weight_row(p, tile, row) + k_begin + col * 8;
+    wlds[i] = row * WROW + col * 16;
+  }
+  // A-operand blocks of this wavefront: k-steps (k_begin + kt*BK + wave*32)/16 + {0,1}, halves 0..MH-1
+  const bf16_t* xptr = p.x + (((size_t)mtile * (p.K >> 4) + ((k_begin + wave * 32) >> 4)) * 2 * 64 + lane) * 8;
+
+  u32x4 wreg[PF][4];
+  u32x4 xreg[PF][2][MH];
+  auto load_stage = [&](int kt, int slot) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) wreg[slot][i] = *(const u32x4*)(wptr[i] + (size_t)kt * BK);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int mh = 0; mh < MH; ++mh)
+        xreg[slot][ks][mh] = *(const u32x4*)(xptr + ((size_t)(kt * (BK / 16) + ks) * 2 + mh) * 512);
+  };
+#pragma unroll
+  for (int s = 0; s < PF; ++s)
+    if (s < KT) load_stage(s, s);
+
+  floatx16 acc[MH][2];
+#pragma unroll
+  for (int mh = 0; mh < MH; ++mh)
+#pragma unroll
+    for (int nh = 0; nh < 2; ++nh)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mh][nh][r] = 0.f;
+
+  const int b_off = (lane & 31) * WROW + (wave * 32 + 8 * (lane >> 5)) * 2;
+  for (int kt0 = 0; kt0 < KT; kt0 += PF) {
+#pragma unroll
+    for (int s = 0; s < PF; ++s) {
+      const int kt = kt0 + s;
+      if (kt < KT) {                                            // uniform over the workgroup
+        unsigned char* buf = smem + (kt & 1) * (BN * WROW);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *(u32x4*)(buf + wlds[i]) = wreg[s][i];
+        u32x4 xc[2][MH];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+          for (int mh = 0; mh < MH; ++mh) xc[ks][mh] = xreg[s][ks][mh];
+        if (kt + PF < KT) load_stage(kt + PF, s);
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+          for (int nh = 0; nh < 2; ++nh) {
+            const u32x4 b = *(const u32x4*)(buf + nh * 32 * WROW + b_off + ks * 32);
+#pragma unroll
+            for (int mh = 0; mh < MH; ++mh)
+              acc[mh][nh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                  __builtin_bit_cast(bf16x8, xc[ks][mh]), __builtin_bit_cast(bf16x8, b), acc[mh][nh], 0, 0, 0);
+          }
+      }
+    }
+  }
+
+  // sum the four wavefronts' partial tiles through LDS
+  __syncthreads();
+  float* red = (float*)smem;
+#pragma unroll
+  for (int mh = 0; mh < MH; ++mh)
+#pragma unroll
+    for (int nh = 0; nh < 2; ++nh)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int tok = mh * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        red[(wave * 64 + tok) * RED_LD + nh * 32 + (lane & 31)] = acc[mh][nh][r];
+      }
+  __syncthreads();
+  if (p.epi == GEMM_EPI_PARTIAL) {
+#pragma unroll
+    for (int e = 0; e < 8 * MH; ++e) {
+      const int idx = tid + 256 * e, tok = idx >> 6, f = idx & 63;
+      const float v = red[tok * RED_LD + f] + red[(64 + tok) * RED_LD + f] + red[(128 + tok) * RED_LD + f] +
+                      red[(192 + tok) * RED_LD + f];
+      const int row = mtile * 64 + tok, n = tile * BN + f;
+      if (row < p.M && n < p.N) p.out_f32[((size_t)split * p.M + row) * p.N + n] = v;
+    }
+  } else {
+    const int I = p.N >> 1;
+#pragma unroll
+    for (int e = 0; e < 4 * MH; ++e) {
+      const int idx = tid + 256 * e, tok = idx >> 5, f = idx & 31;
+      float g = 0.f, u = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        g += red[(w * 64 + tok) * RED_LD + f];
+        u += red[(w * 64 + tok) * RED_LD + 32 + f];
+      }
+      const int row = mtile * 64 + tok, n = tile * 32 + f;
+      if (row < p.M && n < I) p.out_xf[xf_offset(row, n, I)] = f32_to_bf16(g / (1.f + expf(-g)) * u);
+    }
+  }
+}
+
+}  // namespace
+
+int gemm_skinny_pick_splits(int N, int K, int M) {
+  const int tiles = (N + BN - 1) / BN * ((M + 63) / 64);
+  const int KT = K / BK;
+  int best = 1;
+  for (int S = 1; S <= 16; S *= 2) {
+    if (KT % S) break;
+    if (KT / S < 4 && S > 1) break;
+    best = S;
+    if (tiles * S >= 448) break;
+  }
+  return best;
+}
+
+hipError_t launch_gemm_skinny(const bf16_t* x, const GemmWeights& W, int M, int N, int K, int S, int epi, void* out,
+                              hipStream_t st) {
+  if (M <= 0 || N <= 0 || K <= 0 || S <= 0 || K % (BK * S) != 0) return hipErrorInvalidValue;
+  if (epi == GEMM_EPI_SWIGLU && (S != 1 || W.mode != 1)) return hipErrorInvalidValue;
+  GemmParams p;
+  p.x = x;
+  for (int i = 0; i < 3; ++i) { p.w[i] = (const bf16_t*)W.w[i]; p.rows[i] = W.rows[i]; }
+  p.nmat = W.nmat; p.mode = W.mode;
+  p.M = M; p.N = N; p.K = K; p.S = S; p.epi = epi;
+  p.out_f32 = (float*)out; p.out_xf = (bf16_t*)out;
+  const int tiles = W.mode == 1 ? (N / 2 + 31) / 32 : (N + BN - 1) / BN;
+  dim3 grid(tiles, S, (M + 63) / 64);
+  if (M <= 32)
+    hipLaunchKernelGGL(gemm_skinny_kernel<1>, grid, dim3(256), 0, st, p);
+  else
+    hipLaunchKernelGGL(gemm_skinny_kernel<2>, grid, dim3(256), 0, st, p);
+  return hipGetLastError();
+}

@@ -1,0 +1,114 @@
+// Host-side launch interface of the gfx950 kernels (one definition per .hip file).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint16_t bf16_t;
+
+// ---------------------------------------------------------------- GEMM (gemm_skinny.hip, gemm_f32.hip)
+// Weight operand: up to three [rows_i, K] row-major matrices.
+//   mode 0: their rows are concatenated (q|k|v projections run as one GEMM);
+//   mode 1: tiles interleave 32 rows of w[0] (gate) with the same 32 rows of w[1] (up) so that the
+//           SwiGLU product can be formed in the epilogue.
+struct GemmWeights {
+  const void* w[3];
+  int rows[3];
+  int nmat;
+  int mode;
+};
+enum { GEMM_EPI_PARTIAL = 0, GEMM_EPI_SWIGLU = 1 };
+
+// Y = X W^T for few rows (M <= a few hundred) streaming the weights once: bf16 inputs, fp32 accumulate.
+//   x      fragment-major bf16 [ceil64(M), K] (see xf_offset)
+//   out    epi PARTIAL: fp32 [S, M, N] (split-K partial sums, S = splits); the consumer adds them
+//          epi SWIGLU : fragment-major bf16 [ceil64(M), N/2] = silu(gate) * up   (requires S == 1)
+// Requires K % (128*S) == 0.  N = total weight rows.
+hipError_t launch_gemm_skinny(const bf16_t* x, const GemmWeights& W, int M, int N, int K, int S, int epi,
+                              void* out, hipStream_t st);
+// Chooses the split-K factor for a [N, K] weight so that about two workgroups per CU are resident.
+int gemm_skinny_pick_splits(int N, int K, int M);
+
+// fp32 reference-quality GEMM: out[m, col0 + n] = sum_k x[m,k] w[n,k]; x [M,K], w [N,K], out row stride ld.
+hipError_t launch_gemm_f32(const float* x, const float* w, int M, int N, int K, float* out, int ld, int col0,
+                           hipStream_t st);
+
+// ---------------------------------------------------------------- elementwise (elementwise.hip)
+struct SeqInfo {           // one per sequence, device resident
+  int32_t kv_base;         // first cache slot of the sequence
+  int32_t n_prefix;        // slots visible to every row
+  int32_t n_tail;          // following slots, visible according to the per-row bit mask
+  int32_t pad;
+};
+
+hipError_t launch_embed_rows(bool bf16, const void* embed, const int32_t* tok, int R, int k, int vocab, float* x,
+                             hipStream_t st);
+// x += sum_s partial[s]; copies x to each non-null copy_out; act = RMSNorm(x; gain) in the activation layout.
+hipError_t launch_add_norm(bool bf16, float* x, const float* partial, int S, int R, int k, const void* gain, float eps,
+                           void* act, float* const copy_out[4], hipStream_t st);
+// Tree bookkeeping for verification: depth, 128-bit ancestor masks, cache slot and rotary tables per row.
+hipError_t launch_tree_prep(const int32_t* parent, const int32_t* kv_indptr, const int32_t* prefix_len, int B, int N,
+                            int head_dim, float theta, int32_t* depth, uint32_t* mask, int32_t* slot, float* cs,
+                            SeqInfo* seq, hipStream_t st);
+// Rotary tables for rows whose positions are already on the device.
+hipError_t launch_rope_table(const int32_t* pos, int R, int head_dim, float theta, float* cs, hipStream_t st);
+// Sums the q|k|v split-K partials, rotates q and k, writes q (activation type, [R,H,d]) and the cache rows.
+hipError_t launch_rope_kv_write(bool bf16, const float* qkv_partial, int S, int R, int H, int Hkv, int d, const float* cs,
+                                const int32_t* slot, void* q, void* kcache, void* vcache, hipStream_t st);
+hipError_t launch_swiglu_f32(const float* gu, int R, int I, float* h, hipStream_t st);
+hipError_t launch_pack3(bool bf16, const float* a, const float* b, const float* c, int M, int k, void* act, hipStream_t st);
+hipError_t launch_reduce_partials(const float* partial, int S, int M, int N, float* out, hipStream_t st);
+// Draft layer input: act[r] = [RMSNorm(E[tok[r]]; g_embed) ; RMSNorm(f_r; g_feat)], y[r] = f_r,
+// with f_r = feat[src_row ? src_row[r] : r].
+hipError_t launch_draft_input(bool bf16, const void* embed, int vocab, const int32_t* tok, const float* feat,
+                              const int32_t* src_row, int M, int k, const void* g_embed, const void* g_feat, float eps,
+                              void* act, float* y, hipStream_t st);
+// Rows of draft forward 1: positions, slots, causal masks, sequence info.
+hipError_t launch_draft_prep1(const int32_t* kv_indptr, const int32_t* prefix_len, int n_new, int32_t* pos, int32_t* slot,
+                              uint32_t* mask, SeqInfo* seq, hipStream_t st);
+
+// ---------------------------------------------------------------- attention (attention.hip)
+// Tree-masked attention of rows [B * rows_per_seq] against a (ragged) cache.
+//   bf16: q [R,H,d] bf16, cache bf16, out = fragment-major bf16 [R, H*d]; d must be 128.
+//   fp32: q fp32, cache fp32, out row-major fp32.
+// scratch: fp32 workspace of attention_scratch_floats(...) elements.
+size_t attention_scratch_floats(int R, int H, int d, int max_splits);
+int attention_pick_splits(int B, int rows_per_seq, int H, int Hkv, int max_len);
+hipError_t launch_tree_attention(bool bf16, const void* q, const void* kcache, const void* vcache, const SeqInfo* seq,
+                                 const uint32_t* mask, int B, int rows_per_seq, int H, int Hkv, int d, int max_len,
+                                 int n_splits, float* scratch, void* out, hipStream_t st);
+
+// ---------------------------------------------------------------- draft tree (select.hip)
+struct DraftState {          // device arrays owned by the workspace
+  int32_t* pool_tok;         // [pool] draft ids
+  int32_t* pool_parent;      // [pool]
+  int32_t* pool_depth;       // [pool]
+  float* pool_score;         // [pool]
+  uint32_t* pool_mask;       // [pool][4] tail-slot mask of a candidate once it is put on a frontier
+  int32_t* frontier;         // [D][K] pool ids expanded by forward l+1 (row 0 = level-1 candidates)
+  float* top_val;            // [max_rows][K] log-probabilities of the per-row top-K
+  int32_t* top_idx;          // [max_rows][K]
+  // inputs of the next forward
+  int32_t* row_tok;          // [K] target ids
+  int32_t* row_src;          // [K] row of the feature buffer holding the parent's output
+  int32_t* row_pos;          // [K]
+  int32_t* row_slot;         // [K]
+  uint32_t* row_mask;        // [K][4]
+  SeqInfo* seq;              // [1]
+};
+// Per-row log-softmax normaliser and top-K (value desc, id asc) over z[row, 0..V).
+hipError_t launch_topk_rows(const float* z, int ld, int row0, int n_rows, int V, int K, float* top_val, int32_t* top_idx,
+                            hipStream_t st);
+// Level bookkeeping after forward `level` (1-based): writes the new pool entries and, when level < depth,
+// picks the next frontier and the next forward's row inputs.
+hipError_t launch_draft_select(const DraftState& s, const int32_t* d2t, const int32_t* kv_indptr, const int32_t* prefix_len,
+                               int level, int depth, int K, int n_new, int feat_row0, hipStream_t st);
+hipError_t launch_draft_rerank(const DraftState& s, const int32_t* d2t, const int32_t* tok_new, int n_new, int depth, int K,
+                               int n_nodes, int32_t* tree_tok, int32_t* parent, int32_t* node_depth, float* cum_logprob,
+                               int32_t* chosen_dbg, hipStream_t st);
+
+// ---------------------------------------------------------------- acceptance (accept.hip)
+#define ACCEPT_CHUNK 2048
+size_t accept_scratch_floats(int R, int V);
+hipError_t launch_accept(const float* logits, const int32_t* tree_tok, const int32_t* parent, int B, int N, int V,
+                         float temperature, const float* uniforms, float* scratch, int32_t* accept_len, int32_t* path,
+                         int32_t* bonus, hipStream_t st);

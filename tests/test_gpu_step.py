@@ -1,0 +1,153 @@
+"""GPU parity: the library (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Tolerances: 1e-4 max-abs for the fp32 tiny configuration; 2e-2 max-abs on logits and hidden states
+for bf16 configurations; tree structure, indices and accepted lengths bit-exact except where the
+oracle itself reports a near-tie (gap <= 1e-2), which is followed and checked for admissibility."""
+import numpy as np
+import pytest
+import torch
+
+import eagle3_synth as S
+from oracle import eagle3_oracle as O
+import pipeline as PL
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+MID = S.get_shape("c2").with_(name="mid", hidden=512, n_heads=8, n_kv_heads=2, intermediate=1024, vocab=4096,
+                              draft_vocab=2048, n_layers=3, taps=(0, 1, 2), prefix_lo=200, prefix_hi=200, depth=4,
+                              topk=4, n_nodes=24)
+
+
+def _E():
+    import paper_2503_01840_amd as E
+    return E
+
+
+def _tol(shape):
+    return 1e-4 if shape.dtype == "fp32" else 2e-2
+
+
+def _ctx(shape, **kw):
+    E = _E()
+    args = dict(max_batch=1, max_nodes=max(shape.n_nodes, 16), max_depth=shape.depth, max_topk=shape.topk, max_new=8)
+    args.update(kw)
+    ctx = E.Eagle3Context(shape, device=DEV, **args)
+    W = PL.device_weights(shape, device=DEV)
+    ctx.set_weights(W["target"], W["draft"])
+    return ctx
+
+
+def _inputs(shape, model, n_new=None):
+    if shape.dtype == "fp32":
+        return PL.real_prefill_inputs(shape, model)
+    return PL.synthetic_step_inputs(shape, n_new=n_new)
+
+
+def _run_draft(ctx, shape, inp, D, K, N):
+    E = _E()
+    ks, vs, indptr, plen, P = PL.device_kv([inp["draft_kv"]], inp["n_new"] + (D - 1) * K, DEV)
+    kv = E.KVCache(ks, vs, indptr, plen, P)
+    out = E.eagle3_draft_expand(ctx, inp["g_new"].to(DEV), inp["tok_new"].to(DEV), kv, D, K, N, debug=True)
+    torch.cuda.synchronize()
+    return {k: v.cpu().numpy() for k, v in out.items()}, ks[0].float().cpu().numpy(), vs[0].float().cpu().numpy()
+
+
+def _run_verify(ctx, shape, inp, tree_tok, parent, want_hidden=True):
+    E = _E()
+    N = len(tree_tok)
+    pairs = [PL.target_kv_cpu(shape, inp, l) for l in range(shape.n_layers)]
+    ks, vs, indptr, plen, P = PL.device_kv(pairs, N, DEV)
+    kv = E.KVCache(ks, vs, indptr, plen, P)
+    tt = torch.as_tensor(np.asarray(tree_tok), dtype=torch.int32, device=DEV)[None]
+    pp = torch.as_tensor(np.asarray(parent), dtype=torch.int32, device=DEV)[None]
+    logits, taps, hidden = E.eagle3_tree_verify(ctx, tt, pp, kv, want_hidden=True)
+    torch.cuda.synchronize()
+    return logits[0].cpu().numpy(), taps[:, 0].cpu().numpy(), hidden[:, 0].cpu().numpy(), ks, vs, P
+
+
+@pytest.mark.parametrize("shape", [S.get_shape("c1"), MID], ids=lambda s: s.name)
+def test_feature_fusion(shape):
+    E = _E()
+    model = PL.OracleModel(shape)
+    ctx = _ctx(shape)
+    for M in (1, 4, 8):
+        taps = S.normal(S.SEED + M, S.TensorIds.TAPS, (3, M, shape.hidden))
+        ref = O.fuse_features(model.draft()["w_fc"], *[O.as_f64(taps[i]) for i in range(3)], rounding=model.rounding)
+        got = E.eagle3_fuse_features(ctx, *[taps[i].contiguous().to(DEV) for i in range(3)]).cpu().numpy()
+        assert np.max(np.abs(got - ref)) < _tol(shape)
+
+
+@pytest.mark.parametrize("shape,n_new", [(S.get_shape("c1"), 1), (MID, 1), (MID, 3)], ids=["c1", "mid", "mid-3new"])
+def test_draft_expand_matches_oracle(shape, n_new):
+    model = PL.OracleModel(shape)
+    inp = _inputs(shape, model, n_new)
+    ctx = _ctx(shape)
+    D, K, N = shape.depth, shape.topk, shape.n_nodes
+    got, Kg, Vg = _run_draft(ctx, shape, inp, D, K, N)
+    ref = PL.oracle_draft(shape, model, inp, D, K, N,
+                          follow={"pool_tok": got["pool_tok"], "frontier": got["frontier"], "chosen": got["chosen"]})
+    if ref["min_gap"] > 1e-2:
+        assert ref["n_followed"] == 0
+    assert np.array_equal(got["tree_tok"], ref["tree_tok"])
+    assert np.array_equal(got["parent"], ref["parent"])
+    assert np.array_equal(got["depth"], ref["depth"])
+    assert np.array_equal(got["chosen"], ref["chosen"])
+    assert np.array_equal(got["pool_tok"][1:], ref["pool_tok"][1:])
+    assert np.array_equal(got["pool_parent"][1:], ref["pool_parent"][1:])
+    assert np.max(np.abs(got["pool_score"] - ref["pool_score"])) < _tol(shape)
+    assert np.max(np.abs(got["score"] - ref["score"])) < _tol(shape)
+    # the draft cache rows appended by the call
+    n_ctx = inp["draft_kv"][0].shape[0]
+    assert np.max(np.abs(Kg[n_ctx:] - ref["K_cache"][n_ctx:])) < _tol(shape)
+    assert np.max(np.abs(Vg[n_ctx:] - ref["V_cache"][n_ctx:])) < _tol(shape)
+
+
+@pytest.mark.parametrize("shape", [S.get_shape("c1"), MID], ids=lambda s: s.name)
+def test_tree_verify_and_accept_match_oracle(shape):
+    E = _E()
+    model = PL.OracleModel(shape)
+    inp = _inputs(shape, model)
+    D, K, N = shape.depth, shape.topk, shape.n_nodes
+    tree = PL.oracle_draft(shape, model, inp, D, K, N)              # the oracle's own tree is the input
+    ref = PL.oracle_verify(shape, model, inp, tree["tree_tok"], tree["parent"], keep_hidden=True)
+    ctx = _ctx(shape)
+    logits, taps, hidden, ks, vs, P = _run_verify(ctx, shape, inp, tree["tree_tok"], tree["parent"])
+    tol = _tol(shape)
+    for l in range(shape.n_layers + 1):
+        assert np.max(np.abs(hidden[l] - ref["hidden"][l])) < tol, f"residual stream after layer {l - 1}"
+    assert np.max(np.abs(taps - ref["taps"])) < tol
+    assert np.max(np.abs(logits - ref["logits"])) < tol
+    for l in range(shape.n_layers):
+        assert np.max(np.abs(ks[l][P:].float().cpu().numpy() - ref["k_new"][l])) < tol
+        assert np.max(np.abs(vs[l][P:].float().cpu().numpy() - ref["v_new"][l])) < tol
+    # acceptance on the ORACLE's logits (same numbers on both sides)
+    lg = torch.from_numpy(ref["logits"]).float()
+    tt = torch.as_tensor(tree["tree_tok"], dtype=torch.int32, device=DEV)[None]
+    pp = torch.as_tensor(tree["parent"], dtype=torch.int32, device=DEV)[None]
+    al, path, bonus = E.eagle3_accept(ctx, lg.to(DEV)[None].contiguous(), tt, pp, 0.0)
+    n_acc, rpath, rbonus = O.accept_greedy(O.as_f64(lg), tree["tree_tok"], tree["parent"])
+    assert int(al[0]) == n_acc and int(bonus[0]) == rbonus
+    assert path[0].cpu().numpy().tolist() == rpath + [-1] * (N - len(rpath))
+    U = S.uniform01(S.SEED, S.TensorIds.UNIFORMS, (8, 2 * N))
+    for t in range(8):
+        al, path, bonus = E.eagle3_accept(ctx, lg.to(DEV)[None].contiguous(), tt, pp, 1.0, U[t:t + 1].contiguous().to(DEV))
+        n_acc, rpath, rbonus, margin = O.accept_stochastic(O.as_f64(lg), tree["tree_tok"], tree["parent"], 1.0,
+                                                            U[t].double().numpy())
+        if margin > 1e-5:
+            assert (int(al[0]), int(bonus[0])) == (n_acc, rbonus)
+            assert path[0].cpu().numpy().tolist() == rpath + [-1] * (N - len(rpath))
+
+
+def test_results_are_bit_identical_run_to_run():
+    shape = MID
+    model = PL.OracleModel(shape)
+    inp = _inputs(shape, model)
+    ctx = _ctx(shape)
+    a, _, _ = _run_draft(ctx, shape, inp, shape.depth, shape.topk, shape.n_nodes)
+    b, _, _ = _run_draft(ctx, shape, inp, shape.depth, shape.topk, shape.n_nodes)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    l1 = _run_verify(ctx, shape, inp, a["tree_tok"], a["parent"])[0]
+    l2 = _run_verify(ctx, shape, inp, a["tree_tok"], a["parent"])[0]
+    assert np.array_equal(l1, l2)

@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of one EAGLE-3 speculative step on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch: feature fusion, draft-tree
+expansion (depth D, top-K, N-node tree), tree-masked verification through every target layer plus the
+LM head, and the acceptance walk (greedy and temperature 1).  Inputs (random-init LLaMA-shaped weights,
+random KV caches) are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+
+
+def algorithmic_bytes(shape, n_new):
+    """Bytes the method must move per step (weights once per forward, caches once per layer, logits out)."""
+    b = 2 if shape.dtype == "bf16" else 4
+    k, V, Vd, L, N, P, D = shape.hidden, shape.vocab, shape.draft_vocab, shape.n_layers, shape.n_nodes, shape.prefix_lo, shape.depth
+    kv_row = 2 * shape.kv_dim * b
+    layer_w = shape.layer_params() * b
+    verify = L * (layer_w + (P + N) * kv_row) + V * k * b + N * V * 4 + 3 * N * k * 4
+    draft_fwd = shape.draft_layer_params() * b + Vd * k * b + (P + n_new) * kv_row
+    draft = 3 * k * k * b + D * draft_fwd
+    accept = 2 * N * V * 4
+    return {"verify": verify, "draft": draft, "accept": accept, "step": verify + draft + accept}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c3", choices=["c2", "c3", "c5"])
+    ap.add_argument("--n-new", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding): use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import eagle3_synth as S
+    import paper_2503_01840_amd as E
+
+    shape = S.get_shape(args.config)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    P, N, D, K, n_new = shape.prefix_lo, shape.n_nodes, shape.depth, shape.topk, args.n_new
+    ctx = E.Eagle3Context(shape, max_batch=1, max_nodes=64, max_depth=D, max_topk=K, max_new=max(8, n_new), device=dev)
+    T = S.TensorIds
+    tg = S.target_globals(shape, device=dev)
+    target = {"layers": [S.layer_weights(shape, l, device=dev) for l in range(shape.n_layers)], **tg}
+    draft = S.draft_weights(shape, device=dev)
+    ctx.set_weights(target, draft)
+    ks, vs = zip(*[S.kv_layer(shape, l, P + N, device=dev) for l in range(shape.n_layers)])
+    plen = torch.tensor([P], dtype=torch.int32, device=dev)
+    kv = E.KVCache(ks, vs, torch.tensor([0, P + N], dtype=torch.int32, device=dev), plen, P)
+    d_slots = P + n_new + (D - 1) * K
+    dk, dv = S.kv_layer(shape, 0, d_slots, device=dev, draft=True)
+    dkv = E.KVCache([dk], [dv], torch.tensor([0, d_slots], dtype=torch.int32, device=dev), plen, P)
+    taps = S.normal(S.SEED, T.TAPS, (3, n_new, shape.hidden), device=dev)
+    tok_new = S.uniform_ints(S.SEED, T.TOK_NEW, (n_new,), 0, shape.vocab, device=dev)
+    U = S.uniform01(S.SEED, T.UNIFORMS, (1, 2 * N), device=dev)
+    logits = torch.empty(1, N, shape.vocab, dtype=torch.float32, device=dev)
+    tapbuf = torch.empty(3, 1, N, shape.hidden, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+
+    def step(record=False):
+        if record: ev[0].record()
+        g = E.eagle3_fuse_features(ctx, taps[0], taps[1], taps[2])
+        if record: ev[1].record()
+        tree = E.eagle3_draft_expand(ctx, g, tok_new, dkv, D, K, N)
+        if record: ev[2].record()
+        tt, pp = tree["tree_tok"][None], tree["parent"][None]
+        E.eagle3_tree_verify(ctx, tt, pp, kv, logits=logits, taps=tapbuf)
+        if record: ev[3].record()
+        a0 = E.eagle3_accept(ctx, logits, tt, pp, 0.0)
+        a1 = E.eagle3_accept(ctx, logits, tt, pp, 1.0, U)
+        if record: ev[4].record()
+        return a0, a1
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
+
+    # per-call split (events on the stream the kernels run on), outside the timed region
+    parts = [0.0] * 4
+    reps = min(args.steps, 10)
+    for _ in range(reps):
+        step(record=True)
+        torch.cuda.synchronize()
+        for i in range(4):
+            parts[i] += ev[i].elapsed_time(ev[i + 1]) / reps
+
+    # dominant kernel: the weight-streaming GEMM at verification width (HIP events around every launch)
+    ctx.profile_begin()
+    step()
+    torch.cuda.synchronize()
+    g_ms, g_n, g_bytes = ctx.profile_read(1)
+    d_ms, d_n, d_bytes = ctx.profile_read(0)
+    ctx.profile_end()
+
+    ab = algorithmic_bytes(shape, n_new)
+    roofline = {
+        "bound": "hbm", "kernel": "gemm_skinny_kernel<2> (verification GEMMs, 60 activation rows)",
+        "achieved": g_bytes / g_ms / 1e6, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": g_bytes / g_ms / 1e6 / HBM_PEAK_GBPS, "traffic": None,
+        "launches_per_step": g_n, "avg_launch_us": g_ms / g_n * 1e3, "bytes_per_launch": g_bytes / g_n,
+        "draft_gemm_GBps": d_bytes / d_ms / 1e6 if d_ms else None,
+        "step_algorithmic_GB": ab["step"] / 1e9, "step_GBps": ab["step"] / ms_per_step / 1e6,
+        "step_frac_of_hbm_peak": ab["step"] / ms_per_step / 1e6 / HBM_PEAK_GBPS,
+    }
+
+    out = {
+        "metric": "tree tokens verified/s over the whole draft+verify step (8B-shape bs1)",
+        "value": N / ms_per_step * 1e3, "unit": "tree tokens verified/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "step_us": ms_per_step * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.config}: {shape.n_layers}-layer LLaMA-8B-shaped speculative step, batch 1, "
+                               f"prefix {P}, tree N={N} depth={D} top-k={K}, n_new={n_new}, draft vocab {shape.draft_vocab}"
+                   if args.config != "c5" else f"c5: 80-layer LLaMA-70B-shaped step, prefix {P}, N={N}, D={D}, K={K}",
+                   "parallelism": "single GPU"},
+        "call_us": {"fuse_features": parts[0] * 1e3, "draft_expand": parts[1] * 1e3, "tree_verify": parts[2] * 1e3,
+                    "accept_greedy_plus_stochastic": parts[3] * 1e3},
+        "verify_tree_tokens_per_s": N / parts[2] * 1e3,
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape)
+    print(json.dumps(out))
+
+
+def cpu_baseline(shape, n_layers=8):
+    """The oracle as it stands, timed on this machine's host cores over a bounded sample of the same workload:
+    `n_layers` target layers of the tree verification (weights generated beforehand, not timed)."""
+    import numpy as np
+    import eagle3_synth as S
+    from oracle import eagle3_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    N, P = shape.n_nodes, shape.prefix_lo
+    parent, _ = S.random_tree(S.SEED, 0, N, shape.depth, shape.topk)
+    tok = S.uniform_ints(S.SEED, S.TensorIds.TREE_TOK, (N,), 0, shape.vocab).numpy()
+    Ws = [O.weights_f64(S.layer_weights(shape, l)) for l in range(n_layers)]
+    kvs = [tuple(O.as_f64(t) for t in S.kv_layer(shape, l, P)) for l in range(n_layers)]
+    emb = O.as_f64(S.normal(S.SEED, S.TensorIds.EMBED, (shape.vocab, shape.hidden), 0.02, 0.0,
+                            __import__("torch").bfloat16 if shape.dtype == "bf16" else __import__("torch").float32))
+    sub = shape.with_(n_layers=n_layers, taps=(0, 0, 0))
+    t0 = time.perf_counter()
+    O.tree_verify(sub, lambda l: Ws[l], {"embed": emb, "lm_head": None}, tok, parent, lambda l: kvs[l],
+                  rounding="bf16" if shape.dtype == "bf16" else "none")
+    dt = time.perf_counter() - t0
+    est_verify_s = dt / n_layers * shape.n_layers
+    return {"value": N / est_verify_s, "unit": "tree tokens verified/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n_layers} of {shape.n_layers} target layers of the {N}-node tree verification against a "
+                      f"{P}-token cache, fp64 NumPy, {dt:.2f} s measured, scaled to {shape.n_layers} layers "
+                      "(LM head and draft not included)"}
+
+
+if __name__ == "__main__":
+    main()

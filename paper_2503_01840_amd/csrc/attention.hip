@@ -153,11 +153,11 @@ __global__ __launch_bounds__(256, 2) void attn_tree_bf16_kernel(AttnParams p) {
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);
-    const float alpha = exp2f(m_run - m_new);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     float ls = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      s[r] = exp2f(s[r] - m_new);
+      s[r] = __builtin_amdgcn_exp2f(s[r] - m_new);
       ls += s[r];
     }
     ls += __shfl_xor(ls, 32, 64);
@@ -204,20 +204,28 @@ __global__ __launch_bounds__(256, 2) void attn_tree_bf16_kernel(AttnParams p) {
   }
 }
 
-__global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict__ o_part, const float* __restrict__ ml_part,
-                                                        int N, int H, int n_splits, bf16_t* __restrict__ out) {
-  const int h = blockIdx.x % H, r = blockIdx.x / H, b = r / N, node = r % N, d = threadIdx.x;
+// one thread per (row, head, 4 consecutive head-dim entries)
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ o_part, const float* __restrict__ ml_part,
+                                                        int R, int N, int H, int n_splits, bf16_t* __restrict__ out) {
+  const int gid = blockIdx.x * 256 + threadIdx.x;
+  const int d4 = gid & 31, rh = gid >> 5;
+  if (rh >= R * H) return;
+  const int h = rh % H, r = rh / H, b = r / N, node = r % N;
   const size_t base = (((size_t)b * H + h) * n_splits) * N + node;
   float M = NEG;
   for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ml_part[(base + (size_t)s * N) * 2]);
-  float num = 0.f, den = 0.f;
+  float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+  float den = 0.f;
   for (int s = 0; s < n_splits; ++s) {
     const size_t pr = base + (size_t)s * N;
-    const float w = exp2f(ml_part[pr * 2] - M);
-    num += w * o_part[pr * D + d];
-    den += w * ml_part[pr * 2 + 1];
+    const float2 ml = *(const float2*)(ml_part + pr * 2);
+    const float w = __builtin_amdgcn_exp2f(ml.x - M);
+    const float4 o = *(const float4*)(o_part + pr * D + 4 * d4);
+    num.x += w * o.x; num.y += w * o.y; num.z += w * o.z; num.w += w * o.w;
+    den += w * ml.y;
   }
-  out[xf_offset(r, h * D + d, H * D)] = f32_to_bf16(num / den);
+  const float inv = 1.0f / den;
+  Act<true>::store4(out, r, h * D + 4 * d4, H * D, num.x * inv, num.y * inv, num.z * inv, num.w * inv);
 }
 
 // ---------------------------------------------------------------------------------------------- fp32
@@ -268,7 +276,7 @@ int attention_pick_splits(int B, int rows_per_seq, int H, int Hkv, int max_len) 
   const int qblocks = (G * rows_per_seq + 127) / 128;
   const int base = B * Hkv * qblocks;
   const int tiles = (max_len + KT - 1) / KT;
-  int s = (512 + base - 1) / base;               // aim at ~2 workgroups per CU
+  int s = (256 + base - 1) / base;               // aim at one workgroup per CU
   s = s < 1 ? 1 : s;
   const int cap = (tiles + 3) / 4;               // at least 4 key tiles per split
   if (s > cap) s = cap < 1 ? 1 : cap;
@@ -302,7 +310,7 @@ hipError_t launch_tree_attention(bool bf16, const void* q, const void* kcache, c
   hipLaunchKernelGGL(attn_tree_bf16_kernel, dim3(B * p.n_qblocks * n_splits * Hkv), dim3(256), 0, st, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_merge_kernel, dim3(R * H), dim3(128), 0, st, p.o_part, p.ml_part, rows_per_seq, H, n_splits,
-                     (bf16_t*)out);
+  hipLaunchKernelGGL(attn_merge_kernel, dim3((R * H * 32 + 255) / 256), dim3(256), 0, st, p.o_part, p.ml_part, R,
+                     rows_per_seq, H, n_splits, (bf16_t*)out);
   return hipGetLastError();
 }

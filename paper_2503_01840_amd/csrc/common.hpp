@@ -42,11 +42,39 @@ template <bool BF16> struct Act;
 template <> struct Act<true> {
   typedef bf16_t type;
   static __device__ __forceinline__ void store(bf16_t* p, int row, int k, int K, float v) { p[xf_offset(row, k, K)] = f32_to_bf16(v); }
+  // four consecutive k (k % 4 == 0) are contiguous in the fragment-major layout
+  static __device__ __forceinline__ void store4(bf16_t* p, int row, int k, int K, float a, float b, float c, float d) {
+    uint2 v;
+    v.x = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+    v.y = (uint32_t)f32_to_bf16(c) | ((uint32_t)f32_to_bf16(d) << 16);
+    *(uint2*)(p + xf_offset(row, k, K)) = v;
+  }
 };
 template <> struct Act<false> {
   typedef float type;
   static __device__ __forceinline__ void store(float* p, int row, int k, int K, float v) { p[(size_t)row * K + k] = v; }
+  static __device__ __forceinline__ void store4(float* p, int row, int k, int K, float a, float b, float c, float d) {
+    *(float4*)(p + (size_t)row * K + k) = make_float4(a, b, c, d);
+  }
 };
+
+// four consecutive values of a weight-typed vector (gain) or of a row-major activation
+__device__ __forceinline__ float4 load4_f32(const float* p, size_t i) { return *(const float4*)(p + i); }
+__device__ __forceinline__ float4 load4_f32(const bf16_t* p, size_t i) {
+  const uint2 v = *(const uint2*)(p + i);
+  return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xFFFF0000u), __uint_as_float(v.y << 16),
+                     __uint_as_float(v.y & 0xFFFF0000u));
+}
+// four consecutive values stored in the plain (row-major) storage type
+__device__ __forceinline__ void store4_plain(float* p, size_t i, float a, float b, float c, float d) {
+  *(float4*)(p + i) = make_float4(a, b, c, d);
+}
+__device__ __forceinline__ void store4_plain(bf16_t* p, size_t i, float a, float b, float c, float d) {
+  uint2 v;
+  v.x = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+  v.y = (uint32_t)f32_to_bf16(c) | ((uint32_t)f32_to_bf16(d) << 16);
+  *(uint2*)(p + i) = v;
+}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -1,6 +1,8 @@
 // Row-wise kernels between the GEMMs: embedding gather, residual add + RMSNorm, rotary embedding and
 // cache write, tree bookkeeping, SwiGLU (fp32 path), feature packing.  All are tiny next to the weight
 // streams; they exist to hand the next GEMM its operand in the layout it reads.
+#include <algorithm>
+
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -16,27 +18,46 @@ __global__ __launch_bounds__(256) void embed_rows_kernel(const TW* __restrict__ 
 
 struct CopyOut { float* p[4]; };
 
+// One workgroup per row, four consecutive columns per thread (two such groups when k > 4096): the row stays
+// in registers between the partial-sum reduction and the normalised store.
 template <bool BF16>
-__global__ __launch_bounds__(256) void add_norm_kernel(float* __restrict__ x, const float* __restrict__ partial, int S,
-                                                      int R, int k, const typename Act<BF16>::type* __restrict__ gain,
-                                                      float eps, typename Act<BF16>::type* __restrict__ act, CopyOut co) {
+__global__ __launch_bounds__(1024) void add_norm_kernel(float* __restrict__ x, const float* __restrict__ partial, int S,
+                                                       int R, int k, const typename Act<BF16>::type* __restrict__ gain,
+                                                       float eps, typename Act<BF16>::type* __restrict__ act, CopyOut co) {
   __shared__ float red[17];
-  const int r = blockIdx.x;
+  const int r = blockIdx.x, nvec = k >> 2, bd = blockDim.x;
+  constexpr int VPT = 2;
+  float4 val[VPT];
   float ss = 0.f;
-  for (int c = threadIdx.x; c < k; c += 256) {
-    float v = x[(size_t)r * k + c];
-    for (int s = 0; s < S; ++s) v += partial[((size_t)s * R + r) * k + c];
-    x[(size_t)r * k + c] = v;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (co.p[i]) co.p[i][(size_t)r * k + c] = v;
-    ss += v * v;
+  for (int j = 0; j < VPT; ++j) {
+    const int v = threadIdx.x + j * bd;
+    if (v < nvec) {
+      float4 a = *(const float4*)(x + (size_t)r * k + 4 * v);
+      for (int s = 0; s < S; ++s) {
+        const float4 p = *(const float4*)(partial + ((size_t)s * R + r) * k + 4 * v);
+        a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+      }
+      *(float4*)(x + (size_t)r * k + 4 * v) = a;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (co.p[i]) *(float4*)(co.p[i] + (size_t)r * k + 4 * v) = a;
+      ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+      val[j] = a;
+    }
   }
   ss = block_sum(ss, red);
   if (act == nullptr) return;
   const float inv = 1.0f / sqrtf(ss / (float)k + eps);
-  for (int c = threadIdx.x; c < k; c += 256)
-    Act<BF16>::store(act, r, c, k, x[(size_t)r * k + c] * inv * load_f32(gain, c));
+#pragma unroll
+  for (int j = 0; j < VPT; ++j) {
+    const int v = threadIdx.x + j * bd;
+    if (v < nvec) {
+      const float4 g = load4_f32(gain, 4 * v);
+      Act<BF16>::store4(act, r, 4 * v, k, val[j].x * inv * g.x, val[j].y * inv * g.y, val[j].z * inv * g.z,
+                        val[j].w * inv * g.w);
+    }
+  }
 }
 
 // cos/sin of pos * theta^(-2i/d) in fp64, stored fp32: cs[r][i] = cos, cs[r][d/2 + i] = sin
@@ -89,35 +110,40 @@ __global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restri
   for (int e = blockIdx.x * 256 + threadIdx.x; e < R * half; e += gridDim.x * 256) rope_entry(cs, e / half, e % half, d, pos[e / half], theta);
 }
 
+// One workgroup per row; a thread handles four consecutive rotary pairs (i..i+3, i+d/2..i+d/2+3) of one head.
 template <bool BF16>
-__global__ __launch_bounds__(256) void rope_kv_write_kernel(const float* __restrict__ qkv, int S, int R, int H, int Hkv,
-                                                           int d, const float* __restrict__ cs,
-                                                           const int32_t* __restrict__ slot,
-                                                           typename Act<BF16>::type* __restrict__ q,
-                                                           typename Act<BF16>::type* __restrict__ kc,
-                                                           typename Act<BF16>::type* __restrict__ vc) {
+__global__ __launch_bounds__(1024) void rope_kv_write_kernel(const float* __restrict__ qkv, int S, int R, int H, int Hkv,
+                                                            int d, const float* __restrict__ cs,
+                                                            const int32_t* __restrict__ slot,
+                                                            typename Act<BF16>::type* __restrict__ q,
+                                                            typename Act<BF16>::type* __restrict__ kc,
+                                                            typename Act<BF16>::type* __restrict__ vc) {
   typedef typename Act<BF16>::type T;
-  const int r = blockIdx.x, half = d / 2, NT = (H + 2 * Hkv) * d;
+  const int r = blockIdx.x, half = d / 2, NT = (H + 2 * Hkv) * d, q4 = half / 4;
   const size_t sl = (size_t)slot[r];
-  for (int e = threadIdx.x; e < (H + 2 * Hkv) * half; e += 256) {
-    const int h = e / half, i = e % half;
-    float x1 = 0.f, x2 = 0.f;
+  for (int e = threadIdx.x; e < (H + 2 * Hkv) * q4; e += blockDim.x) {
+    const int h = e / q4, i = (e % q4) * 4;
+    float4 x1 = make_float4(0.f, 0.f, 0.f, 0.f), x2 = x1;
     for (int s = 0; s < S; ++s) {
       const float* row = qkv + ((size_t)s * R + r) * NT + h * d;
-      x1 += row[i];
-      x2 += row[i + half];
+      const float4 a = *(const float4*)(row + i), b = *(const float4*)(row + i + half);
+      x1.x += a.x; x1.y += a.y; x1.z += a.z; x1.w += a.w;
+      x2.x += b.x; x2.y += b.y; x2.z += b.z; x2.w += b.w;
     }
+    T* dst;
     if (h < H + Hkv) {
-      const float c = cs[(size_t)r * d + i], sn = cs[(size_t)r * d + half + i];
-      const float o1 = x1 * c - x2 * sn, o2 = x2 * c + x1 * sn;
-      T* dst = h < H ? q + ((size_t)r * H + h) * d : kc + (sl * Hkv + (h - H)) * d;
-      store_from_f32(dst, i, o1);
-      store_from_f32(dst, i + half, o2);
+      const float4 c = *(const float4*)(cs + (size_t)r * d + i), sn = *(const float4*)(cs + (size_t)r * d + half + i);
+      const float4 o1 = make_float4(x1.x * c.x - x2.x * sn.x, x1.y * c.y - x2.y * sn.y, x1.z * c.z - x2.z * sn.z,
+                                    x1.w * c.w - x2.w * sn.w);
+      const float4 o2 = make_float4(x2.x * c.x + x1.x * sn.x, x2.y * c.y + x1.y * sn.y, x2.z * c.z + x1.z * sn.z,
+                                    x2.w * c.w + x1.w * sn.w);
+      x1 = o1; x2 = o2;
+      dst = h < H ? q + ((size_t)r * H + h) * d : kc + (sl * Hkv + (h - H)) * d;
     } else {
-      T* dst = vc + (sl * Hkv + (h - H - Hkv)) * d;
-      store_from_f32(dst, i, x1);
-      store_from_f32(dst, i + half, x2);
+      dst = vc + (sl * Hkv + (h - H - Hkv)) * d;
     }
+    store4_plain(dst, i, x1.x, x1.y, x1.z, x1.w);
+    store4_plain(dst, i + half, x2.x, x2.y, x2.z, x2.w);
   }
 }
 
@@ -214,11 +240,13 @@ hipError_t launch_add_norm(bool bf16, float* x, const float* partial, int S, int
                            void* act, float* const copy_out[4], hipStream_t st) {
   CopyOut co;
   for (int i = 0; i < 4; ++i) co.p[i] = copy_out ? copy_out[i] : nullptr;
+  if (k % 4 || k > 8192) return hipErrorInvalidValue;
+  const int bd = std::min(1024, (k / 4 + 63) / 64 * 64);
   if (bf16)
-    hipLaunchKernelGGL(add_norm_kernel<true>, dim3(R), dim3(256), 0, st, x, partial, S, R, k, (const bf16_t*)gain, eps,
+    hipLaunchKernelGGL(add_norm_kernel<true>, dim3(R), dim3(bd), 0, st, x, partial, S, R, k, (const bf16_t*)gain, eps,
                        (bf16_t*)act, co);
   else
-    hipLaunchKernelGGL(add_norm_kernel<false>, dim3(R), dim3(256), 0, st, x, partial, S, R, k, (const float*)gain, eps,
+    hipLaunchKernelGGL(add_norm_kernel<false>, dim3(R), dim3(bd), 0, st, x, partial, S, R, k, (const float*)gain, eps,
                        (float*)act, co);
   return hipGetLastError();
 }
@@ -240,11 +268,13 @@ hipError_t launch_rope_table(const int32_t* pos, int R, int head_dim, float thet
 
 hipError_t launch_rope_kv_write(bool bf16, const float* qkv_partial, int S, int R, int H, int Hkv, int d, const float* cs,
                                 const int32_t* slot, void* q, void* kcache, void* vcache, hipStream_t st) {
+  if (d % 8) return hipErrorInvalidValue;
+  const int bd = std::min(1024, ((H + 2 * Hkv) * d / 8 + 63) / 64 * 64);
   if (bf16)
-    hipLaunchKernelGGL(rope_kv_write_kernel<true>, dim3(R), dim3(256), 0, st, qkv_partial, S, R, H, Hkv, d, cs, slot,
+    hipLaunchKernelGGL(rope_kv_write_kernel<true>, dim3(R), dim3(bd), 0, st, qkv_partial, S, R, H, Hkv, d, cs, slot,
                        (bf16_t*)q, (bf16_t*)kcache, (bf16_t*)vcache);
   else
-    hipLaunchKernelGGL(rope_kv_write_kernel<false>, dim3(R), dim3(256), 0, st, qkv_partial, S, R, H, Hkv, d, cs, slot,
+    hipLaunchKernelGGL(rope_kv_write_kernel<false>, dim3(R), dim3(bd), 0, st, qkv_partial, S, R, H, Hkv, d, cs, slot,
                        (float*)q, (float*)kcache, (float*)vcache);
   return hipGetLastError();
 }

@@ -15,12 +15,27 @@
 
 namespace {
 
-constexpr int BK = 128;                 // k per stage
+#ifndef GEMM_BK
+#define GEMM_BK 128
+#endif
+constexpr int BK = GEMM_BK;             // k per stage (128 or 256)
+constexpr int WCH = BK / 32;            // 16-byte weight chunks per thread per stage
+constexpr int KSW = BK / 64;            // MFMA k-steps per wavefront per stage
+constexpr int CPR = BK / 8;             // 16-byte chunks per weight row per stage
 constexpr int BN = 64;                  // weight rows per workgroup
 constexpr int WROW = BK * 2 + 16;       // LDS bytes per staged weight row (padded)
-constexpr int PF = 4;                   // stages in flight
+#ifndef GEMM_PF
+#define GEMM_PF 4
+#endif
+#ifndef GEMM_OCC
+#define GEMM_OCC 2
+#endif
+#ifndef GEMM_ROT_MUL
+#define GEMM_ROT_MUL 5
+#endif
+constexpr int PF = GEMM_PF;             // stages in flight
 constexpr int RED_LD = 65;              // floats per row of the reduction buffer
-constexpr int SMEM_BYTES = 4 * 64 * RED_LD * 4;   // >= 2 * BN * WROW
+constexpr int SMEM_BYTES = 4 * 64 * RED_LD * 4 > 2 * BN * WROW ? 4 * 64 * RED_LD * 4 : 2 * BN * WROW;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -47,38 +62,53 @@ __device__ __forceinline__ const bf16_t* weight_row(const GemmParams& p, int til
 }
 
 template <int MH>
-__global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(GemmParams p) {
+__global__ __launch_bounds__(256, GEMM_OCC) void gemm_skinny_kernel(GemmParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tile = blockIdx.x, split = blockIdx.y, mtile = blockIdx.z;
   const int Kc = p.K / p.S, k_begin = split * Kc, KT = Kc / BK;
 
-  const bf16_t* wptr[4];
-  int wlds[4];
+  const bf16_t* wptr[WCH];
+  int wlds[WCH];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int c = tid + 256 * i, row = c >> 4, col = c & 15;
+  for (int i = 0; i < WCH; ++i) {
+    const int c = tid + 256 * i, row = c / CPR, col = c % CPR;
     wptr[i] = weight_row(p, tile, row) + k_begin + col * 8;
     wlds[i] = row * WROW + col * 16;
   }
-  // A-operand blocks of this wavefront: k-steps (k_begin + kt*BK + wave*32)/16 + {0,1}, halves 0..MH-1
-  const bf16_t* xptr = p.x + (((size_t)mtile * (p.K >> 4) + ((k_begin + wave * 32) >> 4)) * 2 * 64 + lane) * 8;
+  // A-operand blocks of this wavefront: k-steps (k_begin + kt*BK + wave*(BK/4))/16 + {0..KSW-1}, halves 0..MH-1
+  const bf16_t* xptr = p.x + (((size_t)mtile * (p.K >> 4) + ((k_begin + wave * (BK / 4)) >> 4)) * 2 * 64 + lane) * 8;
 
-  u32x4 wreg[PF][4];
-  u32x4 xreg[PF][2][MH];
-  auto load_stage = [&](int kt, int slot) {
+  u32x4 wreg[PF][WCH];
+  u32x4 xreg[PF][KSW][MH];
+#ifdef GEMM_NOROT
+  const int rot = 0;
+#else
+  // Workgroups walk their K range from staggered starting stages: with power-of-two row strides, all
+  // workgroups reading the same k offset at the same time would hammer the same few HBM channels.
+  const int rot = (tile * GEMM_ROT_MUL + split) % KT;
+#endif
+  auto load_stage = [&](int kt0_, int slot) {
+    int kt = kt0_ + rot;
+    kt = kt >= KT ? kt - KT : kt;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) wreg[slot][i] = *(const u32x4*)(wptr[i] + (size_t)kt * BK);
+    for (int i = 0; i < WCH; ++i) {
+#ifdef GEMM_NT
+      wreg[slot][i] = __builtin_nontemporal_load((const u32x4*)(wptr[i] + (size_t)kt * BK));
+#else
+      wreg[slot][i] = *(const u32x4*)(wptr[i] + (size_t)kt * BK);
+#endif
+    }
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
+    for (int ks = 0; ks < KSW; ++ks)
 #pragma unroll
       for (int mh = 0; mh < MH; ++mh)
+#ifdef GEMM_NOX
+        xreg[slot][ks][mh] = (u32x4){(uint32_t)kt, 1u, 2u, 3u};
+#else
         xreg[slot][ks][mh] = *(const u32x4*)(xptr + ((size_t)(kt * (BK / 16) + ks) * 2 + mh) * 512);
+#endif
   };
-#pragma unroll
-  for (int s = 0; s < PF; ++s)
-    if (s < KT) load_stage(s, s);
-
   floatx16 acc[MH][2];
 #pragma unroll
   for (int mh = 0; mh < MH; ++mh)
@@ -87,34 +117,60 @@ __global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(GemmParams p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mh][nh][r] = 0.f;
 
-  const int b_off = (lane & 31) * WROW + (wave * 32 + 8 * (lane >> 5)) * 2;
-  for (int kt0 = 0; kt0 < KT; kt0 += PF) {
+  const int b_off = (lane & 31) * WROW + (wave * (BK / 4) + 8 * (lane >> 5)) * 2;
+  // One stage: stage `kt`'s weights go from prefetch slot `s` to LDS, its A operands are set aside, the
+  // slot is refilled with stage kt + PF (when `refill`), and after the barrier the tile is multiplied.
+  auto do_stage = [&](int kt, int s, bool refill) {
+    unsigned char* buf = smem + (kt & 1) * (BN * WROW);
 #pragma unroll
-    for (int s = 0; s < PF; ++s) {
-      const int kt = kt0 + s;
-      if (kt < KT) {                                            // uniform over the workgroup
-        unsigned char* buf = smem + (kt & 1) * (BN * WROW);
+    for (int i = 0; i < WCH; ++i) *(u32x4*)(buf + wlds[i]) = wreg[s][i];
+    u32x4 xc[KSW][MH];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *(u32x4*)(buf + wlds[i]) = wreg[s][i];
-        u32x4 xc[2][MH];
+    for (int ks = 0; ks < KSW; ++ks)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
+      for (int mh = 0; mh < MH; ++mh) xc[ks][mh] = xreg[s][ks][mh];
+    if (refill) load_stage(kt + PF, s);
+    __syncthreads();
 #pragma unroll
-          for (int mh = 0; mh < MH; ++mh) xc[ks][mh] = xreg[s][ks][mh];
-        if (kt + PF < KT) load_stage(kt + PF, s);
-        __syncthreads();
+    for (int ks = 0; ks < KSW; ++ks)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
+      for (int nh = 0; nh < 2; ++nh) {
+        const u32x4 b = *(const u32x4*)(buf + nh * 32 * WROW + b_off + ks * 32);
 #pragma unroll
-          for (int nh = 0; nh < 2; ++nh) {
-            const u32x4 b = *(const u32x4*)(buf + nh * 32 * WROW + b_off + ks * 32);
+        for (int mh = 0; mh < MH; ++mh)
+          acc[mh][nh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              __builtin_bit_cast(bf16x8, xc[ks][mh]), __builtin_bit_cast(bf16x8, b), acc[mh][nh], 0, 0, 0);
+      }
+  };
+  // drain: groups whose refills may not all exist (at most the last two groups of a K range)
+  auto drain = [&](int kt0) {
+    for (; kt0 < KT; kt0 += PF) {
 #pragma unroll
-            for (int mh = 0; mh < MH; ++mh)
-              acc[mh][nh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                  __builtin_bit_cast(bf16x8, xc[ks][mh]), __builtin_bit_cast(bf16x8, b), acc[mh][nh], 0, 0, 0);
-          }
+      for (int s = 0; s < PF; ++s) {
+        const int kt = kt0 + s;
+        if (kt < KT) do_stage(kt, s, kt + PF < KT);
       }
     }
+  };
+  if (KT >= 2 * PF) {
+    // Steady state with no branch between the prologue and the loop body, so that the compiler's wait
+    // counters stay exact and PF-1 stages of loads remain in flight while one is consumed.
+#pragma unroll
+    for (int s = 0; s < PF; ++s) {
+      load_stage(s, s);
+      __builtin_amdgcn_sched_barrier(0);      // keep the issue order: the loop's wait counts depend on it
+    }
+    int kt0 = 0;
+    for (; kt0 + 2 * PF <= KT; kt0 += PF) {
+#pragma unroll
+      for (int s = 0; s < PF; ++s) do_stage(kt0 + s, s, true);
+    }
+    drain(kt0);
+  } else {
+#pragma unroll
+    for (int s = 0; s < PF; ++s)
+      if (s < KT) load_stage(s, s);
+    drain(0);
   }
 
   // sum the four wavefronts' partial tiles through LDS
@@ -158,15 +214,18 @@ __global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(GemmParams p) {
 
 }  // namespace
 
+// Split-K factor: the smallest divisor of the stage count that puts at least ~3/4 of a workgroup per CU
+// in flight (measured on MI355X: 192-256 workgroups already stream a [4096..6144, 4096] weight at its best
+// rate, and every extra split adds an fp32 partial tile the consumer has to read back).
 int gemm_skinny_pick_splits(int N, int K, int M) {
   const int tiles = (N + BN - 1) / BN * ((M + 63) / 64);
   const int KT = K / BK;
   int best = 1;
-  for (int S = 1; S <= 16; S *= 2) {
-    if (KT % S) break;
-    if (KT / S < 4 && S > 1) break;
+  for (int S = 1; S <= 16; ++S) {
+    if (KT % S) continue;
+    if (S > 1 && KT / S < 4) break;
     best = S;
-    if (tiles * S >= 448) break;
+    if (tiles * S >= 192) break;
   }
   return best;
 }

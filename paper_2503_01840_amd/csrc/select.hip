@@ -40,8 +40,50 @@ __device__ __forceinline__ ValIdx block_best(ValIdx x, ValIdx* red) {
   return red[16];
 }
 
+// Row top-K with the row held in registers (V <= 1024 * EPT): every thread keeps the best of its own
+// entries; each of the K rounds is one block-wide arg-max, after which only the winning thread rescans.
+template <int EPT>
 __global__ __launch_bounds__(1024) void topk_rows_kernel(const float* __restrict__ z, int ld, int row0, int V, int K,
                                                         float* __restrict__ top_val, int32_t* __restrict__ top_idx) {
+  __shared__ float red[17];
+  __shared__ ValIdx redv[17];
+  const float* zr = z + (size_t)(row0 + blockIdx.x) * ld;
+  const int tid = threadIdx.x;
+  float v[EPT];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < EPT; ++j) {
+    const int c = tid + j * 1024;
+    v[j] = c < V ? zr[c] : -INFINITY;
+    mx = fmaxf(mx, v[j]);
+  }
+  mx = block_max(mx, red);
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < EPT; ++j) sum += expf(v[j] - mx);          // exp(-inf) = 0 for the padding
+  sum = block_sum(sum, red);
+  const float lse = logf(sum);
+  for (int r = 0; r < K; ++r) {
+    ValIdx b = {-INFINITY, INT_MAX};
+#pragma unroll
+    for (int j = 0; j < EPT; ++j)
+      if (v[j] > b.v) { b.v = v[j]; b.i = tid + j * 1024; }      // ascending index per thread: first maximum kept
+    b = block_best(b, redv);
+    if (tid == 0) {
+      top_val[blockIdx.x * K + r] = b.v - mx - lse;
+      top_idx[blockIdx.x * K + r] = b.i;
+    }
+    if ((b.i & 1023) == tid) {
+#pragma unroll
+      for (int j = 0; j < EPT; ++j)
+        if (j == (b.i >> 10)) v[j] = -INFINITY;
+    }
+  }
+}
+
+// Any V: K passes over the row in global memory.
+__global__ __launch_bounds__(1024) void topk_rows_big_kernel(const float* __restrict__ z, int ld, int row0, int V, int K,
+                                                            float* __restrict__ top_val, int32_t* __restrict__ top_idx) {
   __shared__ float red[17];
   __shared__ ValIdx redv[17];
   const float* zr = z + (size_t)(row0 + blockIdx.x) * ld;
@@ -191,7 +233,12 @@ __global__ __launch_bounds__(1024) void draft_rerank_kernel(DraftState s, const 
 
 hipError_t launch_topk_rows(const float* z, int ld, int row0, int n_rows, int V, int K, float* top_val, int32_t* top_idx,
                             hipStream_t st) {
-  hipLaunchKernelGGL(topk_rows_kernel, dim3(n_rows), dim3(1024), 0, st, z, ld, row0, V, K, top_val, top_idx);
+  if (V <= 8 * 1024)
+    hipLaunchKernelGGL(topk_rows_kernel<8>, dim3(n_rows), dim3(1024), 0, st, z, ld, row0, V, K, top_val, top_idx);
+  else if (V <= 32 * 1024)
+    hipLaunchKernelGGL(topk_rows_kernel<32>, dim3(n_rows), dim3(1024), 0, st, z, ld, row0, V, K, top_val, top_idx);
+  else
+    hipLaunchKernelGGL(topk_rows_big_kernel, dim3(n_rows), dim3(1024), 0, st, z, ld, row0, V, K, top_val, top_idx);
   return hipGetLastError();
 }
 

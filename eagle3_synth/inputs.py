@@ -72,16 +72,18 @@ def _table(std: float, mean: float, dtype: torch.dtype, device: str) -> torch.Te
 _CHUNK = 1 << 23   # hashes per chunk (4 values each)
 
 
-def normal(seed, tid, shape, std=1.0, mean=0.0, dtype=torch.float32, device="cpu"):
-    """Tensor of `shape` whose element i is table[field(i%4) of hash(i//4)]*std+mean, in `dtype`."""
+def normal(seed, tid, shape, std=1.0, mean=0.0, dtype=torch.float32, device="cpu", start=0):
+    """Tensor of `shape` whose flat element i is table[field((start+i)%4) of hash((start+i)//4)]*std+mean, in
+    `dtype`.  `start` (a multiple of 4) selects a window of the tensor's stream, e.g. some rows of a cache."""
     shape = tuple(int(s) for s in shape)
     numel = int(np.prod(shape)) if shape else 1
+    assert start % 4 == 0
     table = _table(float(std), float(mean), dtype, str(device))
     out = torch.empty(numel, dtype=dtype, device=device)
     n_hash = (numel + 3) // 4
     for h0 in range(0, n_hash, _CHUNK):
         cnt = min(_CHUNK, n_hash - h0)
-        h = _hashes(seed, tid, h0, cnt, device)
+        h = _hashes(seed, tid, start // 4 + h0, cnt, device)
         idx = torch.stack([(h >> (16 * f)) & 0xFFFF for f in range(4)], dim=1).reshape(-1)
         lo = 4 * h0
         hi = min(numel, lo + 4 * cnt)
@@ -175,13 +177,29 @@ def draft_weights(shape, seed=SEED, device="cpu"):
     return d
 
 
-def kv_layer(shape, layer, n_tokens, seed=SEED, device="cpu", draft=False):
-    """(K, V) of `n_tokens` cached positions, [n_tokens, Hkv, d], N(0,1) in the storage dtype.
-    K is taken as already rotated (as a cache stores it)."""
+def kv_layer(shape, layer, n_tokens, seed=SEED, device="cpu", draft=False, first_slot=0):
+    """(K, V) of cache slots [first_slot, first_slot + n_tokens), [n_tokens, Hkv, d], N(0,1) in the storage
+    dtype.  K is taken as already rotated (as a cache stores it)."""
     base = TensorIds.DRAFT_KV if draft else TensorIds.KV0 + 2 * layer
     dims = (n_tokens, shape.n_kv_heads, shape.head_dim)
     dt = _tdtype(shape)
-    return normal(seed, base, dims, 1.0, 0.0, dt, device), normal(seed, base + 1, dims, 1.0, 0.0, dt, device)
+    start = first_slot * shape.n_kv_heads * shape.head_dim
+    return (normal(seed, base, dims, 1.0, 0.0, dt, device, start=start),
+            normal(seed, base + 1, dims, 1.0, 0.0, dt, device, start=start))
+
+
+def ragged_batch(shape, seed=SEED):
+    """Seeded batch layout of the ragged-cache configuration: prefix_len[b] uniform in
+    [prefix_lo, prefix_hi], kv_indptr with room for the tree nodes after every prefix, one random tree
+    (at most `topk` children per node, depth <= `depth`) and uniform token ids per sequence."""
+    B, N = shape.batch, shape.n_nodes
+    plen = uniform_ints(seed, TensorIds.PREFIX_LEN, (B,), shape.prefix_lo, shape.prefix_hi + 1).numpy().astype(np.int64)
+    indptr = np.zeros(B + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum(plen + N)
+    parents = np.stack([random_tree(seed, 1000 + b, N, shape.depth, shape.topk)[0] for b in range(B)])
+    toks = uniform_ints(seed, TensorIds.TREE_TOK, (B, N), 0, shape.vocab).numpy()
+    return {"prefix_len": plen.astype(np.int32), "kv_indptr": indptr.astype(np.int32), "parent": parents.astype(np.int32),
+            "tree_tok": toks.astype(np.int32)}
 
 
 def random_tree(seed, salt, n_nodes, max_depth, max_children):

@@ -163,6 +163,18 @@ int eagle3_tree_verify(eagle3_ctx* ctx, int32_t B, int32_t N, const int32_t* tre
                        const eagle3_kv* kv, float* logits, float* taps, float* dbg_hidden,
                        eagle3_stream stream);
 
+/* The same forward restricted to target layers [layer_begin, layer_end): the building block of a
+ * layer-sharded (pipelined) deployment, and the way to check single layers at full size.
+ *   x_in   fp32 [B, N, hidden] residual stream entering layer_begin; NULL = token embeddings
+ *          (then layer_begin must be 0)
+ *   x_out  fp32 [B, N, hidden] residual stream after layer_end - 1, or NULL
+ *   logits fp32 [B, N, vocab] or NULL; non-NULL requires layer_end == n_layers (final norm + LM head)
+ * kv->k / kv->v are indexed by absolute layer number; only entries of the range are read.  At least one
+ * of x_out, logits must be given.  Feature taps are not produced by this call. */
+int eagle3_tree_verify_layers(eagle3_ctx* ctx, int32_t B, int32_t N, const int32_t* tree_tok, const int32_t* parent,
+                              const eagle3_kv* kv, const float* x_in, int32_t layer_begin, int32_t layer_end,
+                              float* x_out, float* logits, eagle3_stream stream);
+
 /* Section 2.1 (accept draft tokens front to back; on the first rejection emit one token from the
  * residual distribution and discard the rest), applied along the tree.  temperature == 0: follow the
  * child equal to the target argmax (ties -> smaller id).  temperature > 0: p = softmax(logits/T);

@@ -427,14 +427,17 @@ def accept_greedy(logits, tree_tok, parent):
         path.append(cur)
 
 
-def accept_stochastic(logits, tree_tok, parent, temperature, U):
+def accept_stochastic(logits, tree_tok, parent, temperature, U, return_info=False):
     """Temperature > 0.  At node `cur` with target distribution p = softmax(logits/T): test its
     children in ascending node id; child c (token t) is accepted with probability
     p[t] / (1 - rejected mass) using U[2c]; a rejected child's token is struck from the residual.
     When no child is accepted the bonus token is drawn by inverse CDF (vocabulary order) from the
     renormalised residual using U[2*cur+1].  Returns (accept_len, path, bonus, margin) where margin is
-    the smallest distance of any uniform used from its decision threshold (in probability units)."""
-    cur, path, margin = 0, [0], np.inf
+    the smallest distance of any uniform used from its decision threshold (in probability units).
+    With return_info a fifth value describes the final draw: the residual CDF (un-normalised, vocabulary
+    order), the target it was searched for, and the margin of the child tests alone, so that a checker can
+    decide whether another implementation's bonus token is admissible within its rounding error."""
+    cur, path, margin, margin_children = 0, [0], np.inf, np.inf
     while True:
         p = softmax(np.asarray(logits[cur], dtype=np.float64) / temperature)
         rej, struck, accepted = 0.0, [], None
@@ -443,6 +446,7 @@ def accept_stochastic(logits, tree_tok, parent, temperature, U):
             thr = p[t] / (1.0 - rej) if t not in struck else 0.0
             r = float(U[2 * c])
             margin = min(margin, abs(r - thr) * (1.0 - rej))
+            margin_children = margin
             if r < thr:
                 accepted = c
                 break
@@ -463,7 +467,20 @@ def accept_stochastic(logits, tree_tok, parent, temperature, U):
         else:                                    # rounding left the running sum short of the target
             bonus = int(np.nonzero(res > 0.0)[0][-1])
         margin = min(margin, float(np.min(np.abs(cdf - target))))
+        if return_info:
+            return len(path) - 1, path, bonus, margin, {"cdf": cdf, "target": target, "residual": res,
+                                                        "margin_children": margin_children}
         return len(path) - 1, path, bonus, margin
+
+
+def bonus_admissible(info, bonus, eps):
+    """True iff `bonus` is a token the inverse-CDF draw could return when every partial sum carries an
+    absolute error of at most eps: it has residual mass and its CDF interval, widened by eps, holds the target."""
+    cdf, target, res = info["cdf"], info["target"], info["residual"]
+    if not (0 <= bonus < len(cdf)) or res[bonus] <= 0.0:
+        return False
+    lo = cdf[bonus] - res[bonus]
+    return lo - eps <= target <= cdf[bonus] + eps
 
 
 # ----------------------------------------------------------------------------- plumbing for whole-step use

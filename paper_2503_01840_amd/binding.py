@@ -17,7 +17,7 @@ EAGLE3_FP32, EAGLE3_BF16 = 0, 1
 EXPORTS = ["eagle3_create", "eagle3_destroy", "eagle3_workspace_bytes", "eagle3_set_workspace", "eagle3_set_weights",
            "eagle3_strerror", "eagle3_last_error", "eagle3_profile_begin", "eagle3_profile_read", "eagle3_profile_end",
            "eagle3_fuse_features", "eagle3_draft_expand",
-           "eagle3_tree_verify", "eagle3_accept"]
+           "eagle3_tree_verify", "eagle3_tree_verify_layers", "eagle3_accept"]
 
 
 class Config(C.Structure):
@@ -79,6 +79,8 @@ def lib():
                                           C.POINTER(DraftDebug), C.c_void_p]
         L.eagle3_tree_verify.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(KV),
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.eagle3_tree_verify_layers.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(KV),
+                                                C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.eagle3_accept.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
@@ -252,6 +254,19 @@ def eagle3_tree_verify(ctx, tree_tok, parent, kv, want_hidden=False, logits=None
     _check(lib().eagle3_tree_verify(ctx._h, B, N, _ptr(tree_tok, torch.int32), _ptr(parent, torch.int32),
                                     C.byref(kv.c), _ptr(logits), _ptr(taps), _ptr(hidden), _stream()))
     return (logits, taps, hidden) if want_hidden else (logits, taps)
+
+
+def eagle3_tree_verify_layers(ctx, tree_tok, parent, kv, x_in, layer_begin, layer_end, want_logits=False):
+    """Layers [layer_begin, layer_end) from the residual stream x_in [B,N,k] (None = embeddings).
+    Returns (x_out, logits or None)."""
+    B, N = tree_tok.shape
+    dev = tree_tok.device
+    x_out = torch.empty(B, N, ctx.cfg.hidden, dtype=torch.float32, device=dev)
+    logits = torch.empty(B, N, ctx.cfg.vocab, dtype=torch.float32, device=dev) if want_logits else None
+    _check(lib().eagle3_tree_verify_layers(ctx._h, B, N, _ptr(tree_tok, torch.int32), _ptr(parent, torch.int32),
+                                           C.byref(kv.c), _ptr(x_in, torch.float32) if x_in is not None else None,
+                                           int(layer_begin), int(layer_end), _ptr(x_out), _ptr(logits), _stream()))
+    return x_out, logits
 
 
 def eagle3_accept(ctx, logits, tree_tok, parent, temperature=0.0, uniforms=None):

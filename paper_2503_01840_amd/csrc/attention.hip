@@ -27,6 +27,7 @@ constexpr int KROW = D * 2 + 16;             // LDS bytes per staged key row
 constexpr int VROW = KT * 2 + 16;            // LDS bytes per transposed value row (one head-dim index)
 constexpr int TILE_BYTES = KT * KROW + D * VROW;
 constexpr float NEG = -1e30f;
+constexpr int PFA = 3;                      // K/V tiles in flight per workgroup
 
 struct AttnParams {
   const bf16_t* q;
@@ -83,30 +84,32 @@ __global__ __launch_bounds__(256, 2) void attn_tree_bf16_kernel(AttnParams p) {
     const int pi = 2 * vp + u;
     vkey[u] = 16 * (pi >> 4) + 8 * ((pi >> 2) & 1) + 4 * ((pi >> 3) & 1) + (pi & 3);
   }
-  u32x4 kreg[2], vreg[2];
-  auto load_tile = [&](int t) {
+  // Register prefetch ring, PFA tiles deep.  Tile indices past the end of the split are clamped to its last
+  // tile (a redundant, harmless load), so the loop body has no branch and the loads stay in flight.
+  u32x4 kreg[PFA][2], vreg[PFA][2];
+  auto load_tile = [&](int t, int slot) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int c = tid + 256 * i;
       const int kk = min(t * KT + (c >> 4), L - 1);
-      kreg[i] = *(const u32x4*)(p.kc + ((size_t)(si.kv_base + kk) * p.Hkv + g) * D + (c & 15) * 8);
+      kreg[slot][i] = *(const u32x4*)(p.kc + ((size_t)(si.kv_base + kk) * p.Hkv + g) * D + (c & 15) * 8);
     }
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const int kk = min(t * KT + vkey[u], L - 1);
-      vreg[u] = *(const u32x4*)(p.vc + ((size_t)(si.kv_base + kk) * p.Hkv + g) * D + vc8 * 8);
+      vreg[slot][u] = *(const u32x4*)(p.vc + ((size_t)(si.kv_base + kk) * p.Hkv + g) * D + vc8 * 8);
     }
   };
-  auto store_tile = [&](unsigned char* buf) {
+  auto store_tile = [&](unsigned char* buf, int slot) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int c = tid + 256 * i;
-      *(u32x4*)(buf + (c >> 4) * KROW + (c & 15) * 16) = kreg[i];
+      *(u32x4*)(buf + (c >> 4) * KROW + (c & 15) * 16) = kreg[slot][i];
     }
     unsigned char* vt = buf + KT * KROW;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const uint32_t a = vreg[0][j], c2 = vreg[1][j];
+      const uint32_t a = vreg[slot][0][j], c2 = vreg[slot][1][j];
       *(uint32_t*)(vt + (vc8 * 8 + 2 * j) * VROW + 4 * vp) = (a & 0xFFFFu) | (c2 << 16);
       *(uint32_t*)(vt + (vc8 * 8 + 2 * j + 1) * VROW + 4 * vp) = (a >> 16) | (c2 & 0xFFFF0000u);
     }
@@ -119,13 +122,13 @@ __global__ __launch_bounds__(256, 2) void attn_tree_bf16_kernel(AttnParams p) {
     for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
   float m_run = NEG, l_run = 0.f;
 
-  if (t_begin < t_end) load_tile(t_begin);
-  for (int t = t_begin; t < t_end; ++t) {
+  const int t_last = max(t_end - 1, 0);
+  auto tile_step = [&](int t, int slot) {
     unsigned char* buf = smem + ((t - t_begin) & 1) * TILE_BYTES;
-    store_tile(buf);
-    if (t + 1 < t_end) load_tile(t + 1);
+    store_tile(buf, slot);
+    load_tile(min(t + PFA, t_last), slot);
     __syncthreads();
-    if (!wave_active) continue;
+    if (!wave_active) return;
     floatx16 s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
@@ -136,20 +139,29 @@ __global__ __launch_bounds__(256, 2) void attn_tree_bf16_kernel(AttnParams p) {
                                                    0, 0);
     }
     const int k0 = t * KT;
-    const bool need_mask = k0 + KT > si.n_prefix;       // tile touches the masked tail or runs past the end
     float mx = NEG;
+    if (k0 + KT > si.n_prefix) {                       // uniform: the tile touches the masked tail or the end
+      // visibility of the tile's 32 keys as one word per lane: bit i <-> key k0 + i
+      const int off0 = k0 - si.n_prefix, w0 = off0 >> 5, sh = off0 & 31;
+      auto word = [&](int i) -> uint32_t {             // i is uniform; keys before the tail are all visible
+        return i < 0 ? 0xFFFFFFFFu : i == 0 ? mw[0] : i == 1 ? mw[1] : i == 2 ? mw[2] : i == 3 ? mw[3] : 0u;
+      };
+      const uint64_t both = ((uint64_t)word(w0 + 1) << 32) | word(w0);
+      uint32_t vis = (uint32_t)(both >> sh);
+      if (L - k0 < 32) vis &= (1u << (L - k0)) - 1u;   // keys past the end of the sequence
+      vis >>= 4 * kg;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float v = s[r] * p.scale_log2;
-      if (need_mask) {
-        const int kk = k0 + 8 * (r >> 2) + 4 * kg + (r & 3);
-        const int off = kk - si.n_prefix;
-        bool vis = kk < L;
-        if (vis && off >= 0) vis = (mw[(off >> 5) & 3] >> (off & 31)) & 1u;
-        v = vis ? v : NEG;
+      for (int r = 0; r < 16; ++r) {
+        const float v = ((vis >> (8 * (r >> 2) + (r & 3))) & 1u) ? s[r] * p.scale_log2 : NEG;
+        s[r] = v;
+        mx = fmaxf(mx, v);
       }
-      s[r] = v;
-      mx = fmaxf(mx, v);
+    } else {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        s[r] *= p.scale_log2;
+        mx = fmaxf(mx, s[r]);
+      }
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);
@@ -169,23 +181,45 @@ __global__ __launch_bounds__(256, 2) void attn_tree_bf16_kernel(AttnParams p) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
     }
-    // P^T as two B operands: operand m holds keys 16m + {4kg..4kg+3, 8+4kg..8+4kg+3} = registers 8m..8m+7
-    u32x4 pf[2];
+    // P^T as B operands: operand m holds keys 16m + {4kg..4kg+3, 8+4kg..8+4kg+3} = registers 8m..8m+7.
+    // exp(S) is split into a bf16 head and a bf16 tail (p = hi + lo, 16 significant bits) and both are
+    // multiplied with V: rounding P to a single bf16 would put a 2^-9 relative error on the attention
+    // output, which the following RMSNorm can magnify when the residual stream is small.
+    u32x4 ph[2], pl[2];
 #pragma unroll
     for (int m = 0; m < 2; ++m)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        pf[m][j] = (uint32_t)f32_to_bf16(s[8 * m + 2 * j]) | ((uint32_t)f32_to_bf16(s[8 * m + 2 * j + 1]) << 16);
+      for (int j = 0; j < 4; ++j) {
+        const float p0 = s[8 * m + 2 * j], p1 = s[8 * m + 2 * j + 1];
+        const bf16_t h0 = f32_to_bf16(p0), h1 = f32_to_bf16(p1);
+        ph[m][j] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+        pl[m][j] = (uint32_t)f32_to_bf16(p0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(p1 - bf16_to_f32(h1)) << 16);
+      }
     const unsigned char* vt = buf + KT * KROW;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
       for (int m = 0; m < 2; ++m) {
         const u32x4 a = *(const u32x4*)(vt + (db * 32 + (lane & 31)) * VROW + (m * 16 + kg * 8) * 2);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, pf[m]),
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, ph[m]),
+                                                       o[db], 0, 0, 0);
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, pl[m]),
                                                        o[db], 0, 0, 0);
       }
+  };
+#pragma unroll
+  for (int sl = 0; sl < PFA; ++sl) {
+    load_tile(min(t_begin + sl, t_last), sl);
+    __builtin_amdgcn_sched_barrier(0);
   }
+  int t = t_begin;
+  for (; t + PFA <= t_end; t += PFA) {
+#pragma unroll
+    for (int sl = 0; sl < PFA; ++sl) tile_step(t + sl, sl);
+  }
+#pragma unroll
+  for (int sl = 0; sl < PFA; ++sl)
+    if (t + sl < t_end) tile_step(t + sl, sl);
 
   if (q_valid) {
     const size_t pr = (((size_t)b * p.H + head) * p.n_splits + split) * N + node;
@@ -213,9 +247,11 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
   const int h = rh % H, r = rh / H, b = r / N, node = r % N;
   const size_t base = (((size_t)b * H + h) * n_splits) * N + node;
   float M = NEG;
+#pragma unroll 8
   for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ml_part[(base + (size_t)s * N) * 2]);
   float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
   float den = 0.f;
+#pragma unroll 8
   for (int s = 0; s < n_splits; ++s) {
     const size_t pr = base + (size_t)s * N;
     const float2 ml = *(const float2*)(ml_part + pr * 2);

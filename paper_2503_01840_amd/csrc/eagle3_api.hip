@@ -326,42 +326,83 @@ static int layer_tail(eagle3_ctx* ctx, const eagle3_layer_weights& w, int B, int
   return EAGLE3_OK;
 }
 
-int eagle3_tree_verify(eagle3_ctx* ctx, int32_t B, int32_t N, const int32_t* tree_tok, const int32_t* parent,
-                       const eagle3_kv* kv, float* logits, float* taps, float* dbg_hidden, eagle3_stream stream) {
-  if (!ctx || !tree_tok || !parent || !kv || !logits || !taps) return EAGLE3_E_NULL;
-  if (!kv->k || !kv->v || !kv->kv_indptr || !kv->prefix_len) return EAGLE3_E_NULL;
-  if (!ctx->ws || !ctx->has_target) return EAGLE3_E_STATE;
+// Layers [l0, l1) of the target stack over the B*N node rows.  x_in == nullptr: start from the token
+// embeddings (requires l0 == 0).  logits != nullptr: finish with the final norm and the LM head (requires
+// l1 == n_layers).  x_out (optional) receives the residual stream after layer l1 - 1.
+static int verify_layers(eagle3_ctx* ctx, int B, int N, const int32_t* tree_tok, const int32_t* parent,
+                         const eagle3_kv* kv, const float* x_in, int l0, int l1, float* x_out, float* logits, float* taps,
+                         float* dbg_hidden, hipStream_t st) {
   const eagle3_config& c = ctx->cfg;
-  if (B < 1 || B > c.max_batch || N < 1 || N > c.max_nodes || kv->max_prefix_len < 0) return EAGLE3_E_SHAPE;
-  for (int l = 0; l < c.n_layers; ++l)
-    if (!kv->k[l] || !kv->v[l]) return EAGLE3_E_NULL;
-  hipStream_t st = (hipStream_t)stream;
   const int R = B * N, k = c.hidden, H = c.n_heads, Hkv = c.n_kv_heads, d = c.head_dim;
   const int max_len = kv->max_prefix_len + N;
   const size_t Rk = (size_t)R * k;
 
   CK(launch_tree_prep(parent, kv->kv_indptr, kv->prefix_len, B, N, d, c.rope_theta, ctx->depth, ctx->mask, ctx->slot,
                       ctx->cs, ctx->seq, st));
-  CK(launch_embed_rows(ctx->bf16, ctx->tw.embed, tree_tok, R, k, c.vocab, ctx->x, st));
+  if (x_in)
+    CK(hipMemcpyAsync(ctx->x, x_in, Rk * sizeof(float), hipMemcpyDeviceToDevice, st));
+  else
+    CK(launch_embed_rows(ctx->bf16, ctx->tw.embed, tree_tok, R, k, c.vocab, ctx->x, st));
   int S_prev = 0;                                   // partial sums of the previous layer's MLP still to be added
-  for (int l = 0; l <= c.n_layers; ++l) {
+  for (int l = l0; l <= l1; ++l) {
     // x becomes the output of layer l-1 here: record taps / debug copies, then norm for what follows
     float* copies[4] = {nullptr, nullptr, nullptr, nullptr};
-    if (l > 0)
+    if (l > 0 && taps)
       for (int t = 0; t < 3; ++t)
         if (c.tap_layers[t] == l - 1) copies[t] = taps + (size_t)t * Rk;
     if (dbg_hidden) copies[3] = dbg_hidden + (size_t)l * Rk;
-    const void* gain = l < c.n_layers ? ctx->layers[l].norm_attn : ctx->tw.final_norm;
+    if (l == l1 && x_out) copies[3] = x_out;
+    const bool head = l == c.n_layers;
+    if (l == l1 && !(head && logits)) {               // the range ends inside the stack: no norm needed
+      CK(launch_add_norm(ctx->bf16, ctx->x, ctx->part, S_prev, R, k, nullptr, c.rms_eps, nullptr, copies, st));
+      break;
+    }
+    const void* gain = head ? ctx->tw.final_norm : ctx->layers[l].norm_attn;
     CK(launch_add_norm(ctx->bf16, ctx->x, ctx->part, S_prev, R, k, gain, c.rms_eps, ctx->act_k, copies, st));
-    if (l == c.n_layers) break;
+    if (l == l1) break;
     const eagle3_layer_weights& w = ctx->layers[l];
     GemmWeights Wqkv = {{w.wq, w.wk, w.wv}, {H * d, Hkv * d, Hkv * d}, 3, 0};
     int S_qkv = 1;
     TRY(ctx->project(ctx->act_k, Wqkv, R, (H + 2 * Hkv) * d, k, GEMM_EPI_PARTIAL, &S_qkv, st));
     TRY(layer_tail(ctx, w, B, N, S_qkv, ctx->slot, ctx->cs, ctx->mask, ctx->seq, kv->k[l], kv->v[l], max_len, &S_prev, st));
   }
-  GemmWeights Wlm = {{ctx->tw.lm_head, nullptr, nullptr}, {c.vocab, 0, 0}, 1, 0};
-  return ctx->project(ctx->act_k, Wlm, R, c.vocab, k, GEMM_EPI_PARTIAL, nullptr, st, logits);
+  if (l1 == c.n_layers && logits) {
+    GemmWeights Wlm = {{ctx->tw.lm_head, nullptr, nullptr}, {c.vocab, 0, 0}, 1, 0};
+    return ctx->project(ctx->act_k, Wlm, R, c.vocab, k, GEMM_EPI_PARTIAL, nullptr, st, logits);
+  }
+  return EAGLE3_OK;
+}
+
+static int check_verify_args(eagle3_ctx* ctx, int B, int N, const int32_t* tree_tok, const int32_t* parent,
+                             const eagle3_kv* kv, int l0, int l1) {
+  if (!ctx || !tree_tok || !parent || !kv) return EAGLE3_E_NULL;
+  if (!kv->k || !kv->v || !kv->kv_indptr || !kv->prefix_len) return EAGLE3_E_NULL;
+  if (!ctx->ws || !ctx->has_target) return EAGLE3_E_STATE;
+  const eagle3_config& c = ctx->cfg;
+  if (B < 1 || B > c.max_batch || N < 1 || N > c.max_nodes || kv->max_prefix_len < 0) return EAGLE3_E_SHAPE;
+  if (l0 < 0 || l1 < l0 || l1 > c.n_layers) return EAGLE3_E_SHAPE;
+  for (int l = l0; l < l1; ++l)
+    if (!kv->k[l] || !kv->v[l]) return EAGLE3_E_NULL;
+  return EAGLE3_OK;
+}
+
+int eagle3_tree_verify(eagle3_ctx* ctx, int32_t B, int32_t N, const int32_t* tree_tok, const int32_t* parent,
+                       const eagle3_kv* kv, float* logits, float* taps, float* dbg_hidden, eagle3_stream stream) {
+  if (!logits || !taps) return EAGLE3_E_NULL;
+  TRY(check_verify_args(ctx, B, N, tree_tok, parent, kv, 0, ctx ? ctx->cfg.n_layers : 0));
+  return verify_layers(ctx, B, N, tree_tok, parent, kv, nullptr, 0, ctx->cfg.n_layers, nullptr, logits, taps, dbg_hidden,
+                       (hipStream_t)stream);
+}
+
+int eagle3_tree_verify_layers(eagle3_ctx* ctx, int32_t B, int32_t N, const int32_t* tree_tok, const int32_t* parent,
+                              const eagle3_kv* kv, const float* x_in, int32_t layer_begin, int32_t layer_end,
+                              float* x_out, float* logits, eagle3_stream stream) {
+  TRY(check_verify_args(ctx, B, N, tree_tok, parent, kv, layer_begin, layer_end));
+  if (!x_in && layer_begin != 0) return EAGLE3_E_NULL;
+  if (!x_out && !logits) return EAGLE3_E_NULL;
+  if (logits && layer_end != ctx->cfg.n_layers) return EAGLE3_E_SHAPE;
+  return verify_layers(ctx, B, N, tree_tok, parent, kv, x_in, layer_begin, layer_end, x_out, logits, nullptr, nullptr,
+                       (hipStream_t)stream);
 }
 
 int eagle3_draft_expand(eagle3_ctx* ctx, const float* g_new, const int32_t* tok_new, int32_t n_new,

@@ -75,7 +75,7 @@ def real_prefill_inputs(shape, model, seed=S.SEED):
     }
 
 
-def oracle_draft(shape, model, inp, depth, topk, n_nodes, follow=None):
+def oracle_draft(shape, model, inp, depth, topk, n_nodes, follow=None, tol=1e-2):
     Kd, Vd = inp["draft_kv"]
     n_ctx = Kd.shape[0]
     cap = n_ctx + inp["n_new"] + (depth - 1) * topk
@@ -83,7 +83,7 @@ def oracle_draft(shape, model, inp, depth, topk, n_nodes, follow=None):
     Kc[:n_ctx], Vc[:n_ctx] = O.as_f64(Kd), O.as_f64(Vd)
     out = O.draft_expand(shape, model.draft(), model.globals()["embed"], O.as_f64(inp["g_new"]),
                          inp["tok_new"].numpy().astype(np.int64), Kc, Vc, n_ctx, depth, topk, n_nodes,
-                         rounding=model.rounding, follow=follow)
+                         rounding=model.rounding, follow=follow, tol=tol)
     out["K_cache"], out["V_cache"] = Kc, Vc
     return out
 

@@ -167,3 +167,14 @@ def test_rejected_sibling_mass_is_removed_from_later_tests_and_from_the_bonus():
     assert (n_acc, path, bonus) == (0, [0], 3)
     U[1] = 0.3            # target .09 <= .1 -> token 0
     assert O.accept_stochastic(logits, tok, parent, 1.0, U)[2] == 0
+
+
+def test_bonus_admissibility_window():
+    parent, tok = np.array([-1, 0]), np.array([0, 2])
+    logits = np.log(np.array([[0.1, 0.2, 0.3, 0.4]] * 2))
+    U = np.array([0, 0.5, 0.99, 0])          # child (p=.3) rejected; residual {.1,.2,0,.4}/.7 ; target = .5*.7 = .35
+    n_acc, path, bonus, margin, info = O.accept_stochastic(logits, tok, parent, 1.0, U, return_info=True)
+    assert (n_acc, bonus) == (0, 3) and abs(info["target"] - 0.35) < 1e-12
+    assert O.bonus_admissible(info, 3, 0.0) and not O.bonus_admissible(info, 1, 0.0)
+    assert O.bonus_admissible(info, 1, 0.06) and not O.bonus_admissible(info, 0, 0.06)    # .30 + .06 >= .35 ; .10 + .06 < .35
+    assert not O.bonus_admissible(info, 2, 1.0)                                           # a struck token never is

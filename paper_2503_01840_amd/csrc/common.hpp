@@ -11,12 +11,15 @@ typedef uint16_t bf16_t;          // raw bfloat16 bits
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 
-// round-to-nearest-even fp32 -> bf16 (inputs are finite in this library)
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float floatx2_t __attribute__((ext_vector_type(2)));
+
+// two fp32 -> two bf16 (round to nearest even) packed into one dword, low half = a: one v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  const floatx2_t f = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
 }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xFFFFu); }
 
 template <typename T> __device__ __forceinline__ float load_f32(const T* p, size_t i);
 template <> __device__ __forceinline__ float load_f32<float>(const float* p, size_t i) { return p[i]; }
@@ -45,8 +48,8 @@ template <> struct Act<true> {
   // four consecutive k (k % 4 == 0) are contiguous in the fragment-major layout
   static __device__ __forceinline__ void store4(bf16_t* p, int row, int k, int K, float a, float b, float c, float d) {
     uint2 v;
-    v.x = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
-    v.y = (uint32_t)f32_to_bf16(c) | ((uint32_t)f32_to_bf16(d) << 16);
+    v.x = pack_bf16x2(a, b);
+    v.y = pack_bf16x2(c, d);
     *(uint2*)(p + xf_offset(row, k, K)) = v;
   }
 };
@@ -71,8 +74,8 @@ __device__ __forceinline__ void store4_plain(float* p, size_t i, float a, float 
 }
 __device__ __forceinline__ void store4_plain(bf16_t* p, size_t i, float a, float b, float c, float d) {
   uint2 v;
-  v.x = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
-  v.y = (uint32_t)f32_to_bf16(c) | ((uint32_t)f32_to_bf16(d) << 16);
+  v.x = pack_bf16x2(a, b);
+  v.y = pack_bf16x2(c, d);
   *(uint2*)(p + i) = v;
 }
 

@@ -109,6 +109,16 @@ struct eagle3_ctx {
   // epi SWIGLU: silu(gate)*up lands in act_h.
   int project(const void* act_in, const GemmWeights& W, int M, int N, int K, int epi, int* S_out, hipStream_t st,
               float* direct_out = nullptr) {
+    if (bf16 && M > 64) {
+      Stamp* sp = profiling && stamps_used < stamps.size() ? &stamps[stamps_used++] : nullptr;
+      if (sp) { sp->bytes = 2.0 * N * K; sp->wide = true; CK(hipEventRecord(sp->a, st)); }
+      int S = 1;
+      void* out = epi == GEMM_EPI_SWIGLU ? act_h : (direct_out ? (void*)direct_out : (void*)part);
+      CK(launch_gemm_wide((const bf16_t*)act_in, W, M, N, K, epi, out, direct_out ? 0 : part_floats, &S, st));
+      if (sp) CK(hipEventRecord(sp->b, st));
+      if (S_out) *S_out = S;
+      return EAGLE3_OK;
+    }
     if (bf16) {
       int S = epi == GEMM_EPI_SWIGLU ? 1 : gemm_skinny_pick_splits(N, K, M);
       while (S > 1 && (size_t)S * M * N > part_floats) S /= 2;
@@ -186,7 +196,8 @@ int eagle3_create(const eagle3_config* cfg, eagle3_ctx** out) {
   ctx->pool_max = 1 + c.max_topk + (c.max_depth - 1) * c.max_topk * c.max_topk;
   const size_t widest = std::max<size_t>({(size_t)(c.n_heads + 2 * c.n_kv_heads) * c.head_dim, (size_t)c.hidden,
                                           ctx->bf16 ? (size_t)0 : (size_t)2 * c.intermediate});
-  ctx->part_floats = std::max<size_t>(1024, 2 * (size_t)ctx->Rall) * widest;
+  // split-K partial sums: up to 4 slices of the widest projection, 8 of a hidden-sized one
+  ctx->part_floats = std::max<size_t>({1024 * widest, 4 * (size_t)ctx->Rall * widest, 8 * (size_t)ctx->Rall * c.hidden});
   size_t af = 0;
   for (int b = 1; b <= c.max_batch; ++b) {
     const int s = attention_pick_splits(b, c.max_nodes, c.n_heads, c.n_kv_heads, 1 << 30);

@@ -28,6 +28,11 @@ hipError_t launch_gemm_skinny(const bf16_t* x, const GemmWeights& W, int M, int 
 // Chooses the split-K factor for a [N, K] weight so that about two workgroups per CU are resident.
 int gemm_skinny_pick_splits(int N, int K, int M);
 
+// The same product for many rows (M > 64): MFMA-bound tiling, see gemm_wide.hip.  Chooses tile shape and split-K
+// itself (S <= what fits into out_capacity_floats; 0 forces S = 1) and reports S.
+hipError_t launch_gemm_wide(const bf16_t* x, const GemmWeights& W, int M, int N, int K, int epi, void* out,
+                            size_t out_capacity_floats, int* S_out, hipStream_t st);
+
 // fp32 reference-quality GEMM: out[m, col0 + n] = sum_k x[m,k] w[n,k]; x [M,K], w [N,K], out row stride ld.
 hipError_t launch_gemm_f32(const float* x, const float* w, int M, int N, int K, float* out, int ld, int col0,
                            hipStream_t st);

@@ -101,6 +101,34 @@ def test_verify_ragged_batch_matches_per_sequence_oracle():
         assert np.max(np.abs(taps[:, b].cpu().numpy() - ref["taps"])) < 2e-2, b
 
 
+def test_verify_more_than_64_rows_uses_the_wide_gemm_path():
+    """12 sequences x 8 nodes = 96 rows (the batched-verification GEMM tiling), 16 x 16 = 256 rows with a ragged tail."""
+    E = _E()
+    shape = SMALL
+    model = PL.OracleModel(shape)
+    for B, N in ((12, 8), (16, 16), (5, 13)):
+        ctx = _ctx(shape, max_batch=B, max_nodes=N)
+        plens = [(37 * b + 11) % 150 for b in range(B)]
+        parents = np.stack([S.random_tree(S.SEED, 80 + b, N, 4, 3)[0] for b in range(B)])
+        toks = S.uniform_ints(S.SEED + B, S.TensorIds.TREE_TOK, (B, N), 0, shape.vocab).numpy()
+        indptr = np.zeros(B + 1, dtype=np.int64)
+        indptr[1:] = np.cumsum(np.array(plens) + N)
+        total = int(indptr[-1])
+        ks, vs = zip(*[tuple(t.to(DEV) for t in S.kv_layer(shape, l, total)) for l in range(shape.n_layers)])
+        kv = E.KVCache(ks, vs, torch.as_tensor(indptr, dtype=torch.int32, device=DEV),
+                       torch.tensor(plens, dtype=torch.int32, device=DEV), max(plens))
+        logits, taps = E.eagle3_tree_verify(ctx, torch.as_tensor(toks, dtype=torch.int32, device=DEV),
+                                            torch.as_tensor(parents, dtype=torch.int32, device=DEV), kv)
+        torch.cuda.synchronize()
+        for b in (0, B // 2, B - 1):
+            base, P = int(indptr[b]), plens[b]
+            ref = O.tree_verify(shape, model.layer, model.globals(), toks[b], parents[b],
+                                lambda l: tuple(O.as_f64(t) for t in S.kv_layer(shape, l, P, first_slot=base)),
+                                rounding="bf16")
+            assert np.max(np.abs(logits[b].cpu().numpy() - ref["logits"])) < 2e-2, (B, N, b)
+            assert np.max(np.abs(taps[:, b].cpu().numpy() - ref["taps"])) < 2e-2, (B, N, b)
+
+
 @pytest.mark.parametrize("n_new,D,K,N", [(8, 3, 3, 10), (1, 4, 1, 5), (2, 1, 4, 5), (1, 2, 16, 40), (3, 8, 2, 30)])
 def test_draft_expand_shapes(n_new, D, K, N):
     E = _E()

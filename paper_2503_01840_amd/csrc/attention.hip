@@ -5,15 +5,23 @@
 // was derived from the parent array: no dense rows x keys mask exists anywhere.
 //
 // bf16 kernel (head_dim 128): flash-style, split over the key range.
-//   * workgroup = (sequence, KV head, block of 128 query rows of that KV head's group, key split);
+//   * workgroup = (sequence, KV head, block of 32 CW query rows of that KV head's group, key split);
 //     the rows of one KV head's group are (query head in group, node) pairs, so all of them share
-//     the K/V tiles staged in LDS;
-//   * each wavefront owns 32 query rows.  Scores are produced transposed, S^T = K Q^T, with
-//     v_mfma_f32_32x32x16_bf16, so a lane holds 16 keys of ONE query: the running max / sum need a
-//     single cross-lane exchange and exp(S^T) is already in B-operand position for O^T += V^T P^T;
-//   * V tiles are transposed on their way into LDS (keys permuted to match that operand order);
-//   * partial (max, sum, O) per split go to scratch; a second kernel merges the splits and writes the
-//     result in the fragment-major layout the output projection reads.
+//     the K/V tiles staged in LDS.  CW is 1, 2 or 4 according to how many such rows there are: many
+//     short-row workgroups (batched verification) pack two to a CU, a single long one fills it;
+//   * K/V tiles of 64 keys reach LDS by direct global-to-LDS loads (1 KiB per wavefront instruction =
+//     four 256-byte cache rows) into a ring of tiles, issued a whole ring ahead: no staging registers, no
+//     LDS store instructions.  Which 16-byte piece of a row a lane fetches is XOR-swizzled with the key
+//     index so that the operand reads below touch every LDS bank once;
+//   * each wavefront owns 32 query rows and one 32-key block of every tile.  Scores are produced
+//     transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16, so a lane holds 16 keys of ONE query: the
+//     running max / sum need a single cross-lane exchange and exp(S^T) is already in B-operand position
+//     for O^T += V^T P^T.  The V^T operand (8 keys of one head-dim index per lane) is read from the
+//     row-major V tile with the transposing LDS read (ds_read_b64_tr_b16: 16 lanes hand in 4 key rows x
+//     16 head-dim values and get back 4 keys of one head-dim value each);
+//   * the two key-block halves are merged through LDS at the end; partial (max, sum, O) per split go to
+//     scratch; a second kernel merges the splits and writes the result in the fragment-major layout the
+//     output projection reads.
 // fp32 kernel: one workgroup per (row, head), scores in LDS; exact arithmetic for the tiny model.
 #include "common.hpp"
 #include "kernels.hpp"
@@ -21,13 +29,12 @@
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
 constexpr int D = 128;
-constexpr int KT = 64;                       // keys per tile = two 32-key score blocks worked on together
-constexpr int KROW = D * 2 + 16;             // LDS bytes per staged key row
-constexpr int VROW = KT * 2 + 16;            // LDS bytes per transposed value row (one head-dim index)
-constexpr int TILE_BYTES = KT * KROW + D * VROW;
+constexpr int KT = 64;                       // keys per tile = two 32-key score blocks
+constexpr int ROWB = D * 2;                  // bytes per cache row
+constexpr int TILE_BYTES = 2 * KT * ROWB;    // K tile, then V tile
 constexpr float NEG = -1e30f;
-constexpr int PFA = 2;                       // K/V tiles in flight per workgroup (register ring)
 
 struct AttnParams {
   const bf16_t* q;
@@ -48,14 +55,32 @@ __device__ __forceinline__ void pair_values(float x, float& a, float& b) {
   b = __uint_as_float(r[1]);
 }
 
-// 8 wavefronts.  Wavefront w works on query rows 32 (w & 3) .. +31 and on key block sb = w >> 2 (32 of the 64
+// One wavefront-wide direct load: lane l's 16 bytes at `src` land at LDS byte address lds_base + 16 l.
+// The compiler does not see these as memory operations; the kernel counts them itself (s_waitcnt vmcnt).
+// (m0 carries the LDS address; naming it as clobbered is what is meant, the compiler's remark about reserved
+// registers on a clobber list is switched off for this one statement.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void dma16(const void* src, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+#define ATTN_WAIT_LOADS(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
+
+constexpr int attn_ring(int CW) { return CW == 4 ? 4 : 2; }
+
+// 2 CW wavefronts.  Wavefront w works on query rows 32 (w >> 1) .. +31 and on key block sb = w & 1 (32 of the 64
 // keys) of every tile, with its own running max / sum / output: the serial chain per tile (8 score MFMAs,
-// softmax, 16 value MFMAs) is what bounds this kernel, so it is cut in two and the halves are merged through
-// LDS at the end.  All 512 threads stage the K/V tiles.
-__global__ __launch_bounds__(512, 1) void attn_tree_bf16_kernel(AttnParams p) {
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * TILE_BYTES];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int cw = wave & 3, sb = wave >> 2;
+// softmax, 16 value MFMAs) is what bounds a wavefront, so it is cut in two and the halves are merged through
+// LDS at the end.
+template <int CW>
+__global__ __launch_bounds__(128 * CW) void attn_tree_bf16_kernel(AttnParams p) {
+  constexpr int NW = 2 * CW, RD = attn_ring(CW);
+  constexpr int IPW = 16 / NW;                 // direct loads per wavefront per tile, for K and again for V
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int cw = wave >> 1, sb = wave & 1;
   int idx = blockIdx.x;
   const int g = idx % p.Hkv; idx /= p.Hkv;
   const int split = idx % p.n_splits; idx /= p.n_splits;
@@ -66,11 +91,11 @@ __global__ __launch_bounds__(512, 1) void attn_tree_bf16_kernel(AttnParams p) {
   const int L = si.n_prefix + si.n_tail;
 
   // this lane's query: row rho of the KV head's group
-  const int rho = qb * 128 + cw * 32 + (lane & 31);
+  const int rho = (qb * CW + cw) * 32 + (lane & 31);
   const bool q_valid = rho < G * N;
   const int head = g * G + (q_valid ? rho / N : 0), node = q_valid ? rho % N : 0;
   const int row = b * N + node;
-  const bool wave_active = qb * 128 + cw * 32 < G * N;
+  const bool wave_active = (qb * CW + cw) * 32 < G * N;
   const int kg = lane >> 5;
 
   u32x4 qf[8];
@@ -82,54 +107,50 @@ __global__ __launch_bounds__(512, 1) void attn_tree_bf16_kernel(AttnParams p) {
   uint32_t mw[4];
 #pragma unroll
   for (int w = 0; w < 4; ++w) mw[w] = p.mask[(size_t)row * 4 + w];
+  ATTN_WAIT_LOADS(0);                          // from here on the only loads in flight are the direct ones below
 
   const int n_tiles = (L + KT - 1) / KT;
   const int tps = (n_tiles + p.n_splits - 1) / p.n_splits;
   const int t_begin = split * tps, t_end = min(n_tiles, t_begin + tps);
   const int t_last = max(t_end - 1, 0);
 
-  // Staging roles.  K: 16-byte chunks c = tid + 512 i (key = c >> 4, column = c & 15).
-  // V: head-dim chunk vc8 = tid & 15 and the key pair pp = tid >> 4 at permuted positions 2pp, 2pp+1, where
-  // position pi = 32 sb + 16 m + 8 kg + 4 g + e holds key 32 sb + 16 m + 8 g + 4 kg + e: the order in which the
-  // P^T operand of the second MFMA carries the keys of score block sb.
-  const int vc8 = tid & 15, pp = tid >> 4;
-  int vkey[2];
+  // Direct loads.  Instruction j (0..15) of a tile brings keys 4j .. 4j+3; lane l fetches, for key 4j + (l >> 4),
+  // the piece that belongs at position l & 15 of the swizzled row: K rows hold piece c at position c ^ (key & 15),
+  // V rows hold piece c at position c ^ ((key & 3) << 2).  Keys past the end of the sequence are clamped to its
+  // last key (masked later); tiles past the end of the split repeat its last tile into a slot nobody reads.
+  const size_t row_stride = (size_t)p.Hkv * D;                        // elements between consecutive cache slots
+  const bf16_t* kbase = p.kc + ((size_t)si.kv_base * p.Hkv + g) * D;
+  const bf16_t* vbase = p.vc + ((size_t)si.kv_base * p.Hkv + g) * D;
+  const int lkey = lane >> 4;
+  const int vpiece = (lane & 15) ^ ((lkey & 3) << 2);
+  auto issue_tile = [&](int t) {
+    const int tt = min(t, t_last);
+    const uint32_t slot = lds0 + ((t - t_begin) % RD) * TILE_BYTES;
 #pragma unroll
-  for (int w = 0; w < 2; ++w) {
-    const int pi = 2 * pp + w;
-    vkey[w] = (pi & 48) + 8 * ((pi >> 2) & 1) + 4 * ((pi >> 3) & 1) + (pi & 3);
-  }
-  // Register prefetch ring, PFA tiles deep.  Tile indices past the end of the split are clamped to its last
-  // tile (a redundant, harmless load), so the loop body has no branch and the loads stay in flight.
-  u32x4 kreg[PFA][2], vreg[PFA][2];
-  auto load_tile = [&](int t, int slot) {
-    t = min(t, t_last);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = tid + 512 * i;
-      const int kk = min(t * KT + (c >> 4), L - 1);
-      kreg[slot][i] = *(const u32x4*)(p.kc + ((size_t)(si.kv_base + kk) * p.Hkv + g) * D + (c & 15) * 8);
+    for (int i = 0; i < IPW; ++i) {
+      const int j = wave * IPW + i;
+      const int key = max(min(tt * KT + 4 * j + lkey, L - 1), 0);
+      const int kpiece = (lane & 15) ^ (4 * (j & 3) + lkey);
+      dma16(kbase + (size_t)key * row_stride + kpiece * 8, slot + j * 1024);
     }
 #pragma unroll
-    for (int w = 0; w < 2; ++w) {
-      const int kk = min(t * KT + vkey[w], L - 1);
-      vreg[slot][w] = *(const u32x4*)(p.vc + ((size_t)(si.kv_base + kk) * p.Hkv + g) * D + vc8 * 8);
+    for (int i = 0; i < IPW; ++i) {
+      const int j = wave * IPW + i;
+      const int key = max(min(tt * KT + 4 * j + lkey, L - 1), 0);
+      dma16(vbase + (size_t)key * row_stride + vpiece * 8, slot + KT * ROWB + j * 1024);
     }
   };
-  auto store_tile = [&](unsigned char* buf, int slot) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = tid + 512 * i;
-      *(u32x4*)(buf + (c >> 4) * KROW + (c & 15) * 16) = kreg[slot][i];
-    }
-    unsigned char* vt = buf + KT * KROW;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t a = vreg[slot][0][j], c2 = vreg[slot][1][j];
-      *(uint32_t*)(vt + (vc8 * 8 + 2 * j) * VROW + 4 * pp) = (a & 0xFFFFu) | (c2 << 16);
-      *(uint32_t*)(vt + (vc8 * 8 + 2 * j + 1) * VROW + 4 * pp) = (a >> 16) | (c2 & 0xFFFF0000u);
-    }
-  };
+
+  // LDS read offsets inside a tile.  K operand (32 keys x 16 k): lane (key = l & 31, pieces 2 ks + kg).
+  const int kkey = sb * 32 + (lane & 31);
+  const int k_off = kkey * ROWB, k_swz = kkey & 15;
+  // V^T operand via transposing reads: call c of k-step m returns, for head-dim index db * 32 + (l & 31), keys
+  // 16 m + 8 c + 4 kg + 0..3 of the block; the lane hands in the address of 4 head-dim values of ONE of those keys:
+  // key + ((l & 15) >> 2), head-dim chunk 16 ((l >> 4) & 1) + 4 (l & 3).
+  const int vkey0 = sb * 32 + 4 * kg + ((lane & 15) >> 2);            // + 16 m + 8 c
+  const int v_swz = (vkey0 & 3) << 2;                                 // (key & 3) does not depend on m, c
+  const int vcol = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);         // piece within the 32-wide head-dim block
+  const int v_half = (lane & 1) * 8;
 
   floatx16 o[4];
 #pragma unroll
@@ -138,25 +159,17 @@ __global__ __launch_bounds__(512, 1) void attn_tree_bf16_kernel(AttnParams p) {
     for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
   float m_run = NEG, l_run = 0.f;
 
-  auto tile_step = [&](int t, int slot) {
-    unsigned char* buf = smem + ((t - t_begin) & 1) * TILE_BYTES;
-#ifndef ATTN_NO_STAGE
-    store_tile(buf, slot);
-    load_tile(t + PFA, slot);
-#endif
-    __syncthreads();
-#ifdef ATTN_NO_COMPUTE
-    return;
-#endif
-    if (!wave_active) return;
+  auto compute_tile = [&](int t) {
+    const unsigned char* kt = smem + ((t - t_begin) % RD) * TILE_BYTES;
+    const unsigned char* vt = kt + KT * ROWB;
     // S^T = K Q^T for this wavefront's 32-key block, as two interleaved chains over the head dimension
     floatx16 s, s2;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { s[r] = 0.f; s2[r] = 0.f; }
 #pragma unroll
     for (int ks = 0; ks < 8; ks += 2) {
-      const u32x4 a0 = *(const u32x4*)(buf + (sb * 32 + (lane & 31)) * KROW + (ks * 16 + kg * 8) * 2);
-      const u32x4 a1 = *(const u32x4*)(buf + (sb * 32 + (lane & 31)) * KROW + ((ks + 1) * 16 + kg * 8) * 2);
+      const u32x4 a0 = *(const u32x4*)(kt + k_off + (((2 * ks + kg) ^ k_swz) * 16));
+      const u32x4 a1 = *(const u32x4*)(kt + k_off + (((2 * ks + 2 + kg) ^ k_swz) * 16));
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), __builtin_bit_cast(bf16x8, qf[ks]), s, 0, 0, 0);
       s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), __builtin_bit_cast(bf16x8, qf[ks + 1]), s2, 0, 0, 0);
     }
@@ -208,7 +221,6 @@ __global__ __launch_bounds__(512, 1) void attn_tree_bf16_kernel(AttnParams p) {
     // exp(S) is split into a bf16 head and a bf16 tail (p = hi + lo, 16 significant bits) and both are
     // multiplied with V: rounding P to a single bf16 would put a 2^-9 relative error on the attention output,
     // which the following RMSNorm can magnify when the residual stream is small.
-    const unsigned char* vt = buf + KT * KROW;
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
       u32x4 ph, pl;
@@ -221,7 +233,14 @@ __global__ __launch_bounds__(512, 1) void attn_tree_bf16_kernel(AttnParams p) {
       }
 #pragma unroll
       for (int db = 0; db < 4; ++db) {
-        const u32x4 a = *(const u32x4*)(vt + (db * 32 + (lane & 31)) * VROW + (sb * 32 + m * 16 + kg * 8) * 2);
+        short4v lo4, hi4;
+        {
+          const unsigned char* a0 = vt + (vkey0 + 16 * m) * ROWB + (((db * 4 + vcol) ^ v_swz) * 16) + v_half;
+          lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(__attribute__((address_space(3))) unsigned char*)a0);
+          hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(__attribute__((address_space(3))) unsigned char*)(a0 + 8 * ROWB));
+        }
+        typedef short short8v __attribute__((ext_vector_type(8)));
+        const short8v a = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
         o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, ph),
                                                        o[db], 0, 0, 0);
         o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, pl),
@@ -229,21 +248,21 @@ __global__ __launch_bounds__(512, 1) void attn_tree_bf16_kernel(AttnParams p) {
       }
     }
   };
-#pragma unroll
-  for (int sl = 0; sl < PFA; ++sl) {
-    load_tile(t_begin + sl, sl);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  int t = t_begin;
-  for (; t + PFA <= t_end; t += PFA) {
-#pragma unroll
-    for (int sl = 0; sl < PFA; ++sl) tile_step(t + sl, sl);
-  }
-#pragma unroll
-  for (int sl = 0; sl < PFA; ++sl)
-    if (t + sl < t_end) tile_step(t + sl, sl);
 
-  // merge the two key-block halves: wavefronts 4-7 hand their state to wavefronts 0-3 through LDS
+  // Ring of RD tiles: tiles t_begin .. t_begin + RD - 2 first, then per iteration the tile RD - 1 ahead, into the
+  // slot that the barrier has just freed.  Loads complete in issue order, so "at most (RD - 2) tiles' worth of my
+  // loads in flight" means that my part of tile t has landed; the barrier extends that to every wavefront's part.
+#pragma unroll
+  for (int i = 0; i < RD - 1; ++i) issue_tile(t_begin + i);
+  for (int t = t_begin; t < t_end; ++t) {
+    ATTN_WAIT_LOADS((RD - 2) * 2 * IPW);
+    __syncthreads();
+    issue_tile(t + RD - 1);
+    if (wave_active) compute_tile(t);
+  }
+  ATTN_WAIT_LOADS(0);                          // nothing may still be writing LDS when it is reused or released
+
+  // merge the two key-block halves: the sb = 1 wavefronts hand their state to their sb = 0 partners through LDS
   __syncthreads();
   float* xo = (float*)smem + (size_t)cw * (66 * 64);           // [64 output registers + m + l][64 lanes]
   if (sb == 1) {
@@ -364,12 +383,15 @@ __global__ __launch_bounds__(256) void attn_tree_f32_kernel(const float* __restr
 
 }  // namespace
 
+static int attn_cw(int rows_per_group) { return rows_per_group <= 32 ? 1 : rows_per_group <= 64 ? 2 : 4; }
+
 int attention_pick_splits(int B, int rows_per_seq, int H, int Hkv, int max_len) {
-  const int G = H / Hkv;
-  const int qblocks = (G * rows_per_seq + 127) / 128;
+  const int G = H / Hkv, cw = attn_cw(G * rows_per_seq);
+  const int qblocks = (G * rows_per_seq + 32 * cw - 1) / (32 * cw);
   const int base = B * Hkv * qblocks;
   const int tiles = (max_len + KT - 1) / KT;
-  int s = (256 + base - 1) / base;               // aim at one workgroup per CU
+  const int slots = cw == 4 ? 256 : 512;         // workgroups resident at once
+  int s = (slots + base - 1) / base;
   s = s < 1 ? 1 : s;
   const int cap = (tiles + 3) / 4;               // at least 4 key tiles per split
   if (s > cap) s = cap < 1 ? 1 : cap;
@@ -378,6 +400,21 @@ int attention_pick_splits(int B, int rows_per_seq, int H, int Hkv, int max_len) 
 
 size_t attention_scratch_floats(int R, int H, int d, int max_splits) {
   return (size_t)R * H * max_splits * (d + 2);
+}
+
+template <int CW>
+static hipError_t launch_attn_cw(const AttnParams& p, int grid, hipStream_t st) {
+  constexpr int LDS = attn_ring(CW) * TILE_BYTES;
+  static_assert(LDS >= CW * 66 * 64 * 4, "the end-of-kernel merge reuses the tile ring");
+  auto kernel = attn_tree_bf16_kernel<CW>;
+  static bool configured = false;                // per process; the attribute belongs to the code object
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(128 * CW), LDS, st, p);
+  return hipGetLastError();
 }
 
 hipError_t launch_tree_attention(bool bf16, const void* q, const void* kcache, const void* vcache, const SeqInfo* seq,
@@ -392,16 +429,17 @@ hipError_t launch_tree_attention(bool bf16, const void* q, const void* kcache, c
     return hipGetLastError();
   }
   if (d != D || H % Hkv) return hipErrorInvalidValue;
+  const int cw = attn_cw(H / Hkv * rows_per_seq);
   AttnParams p;
   p.q = (const bf16_t*)q; p.kc = (const bf16_t*)kcache; p.vc = (const bf16_t*)vcache;
   p.seq = seq; p.mask = mask;
   p.B = B; p.N = rows_per_seq; p.H = H; p.Hkv = Hkv; p.n_splits = n_splits;
-  p.n_qblocks = (H / Hkv * rows_per_seq + 127) / 128;
+  p.n_qblocks = (H / Hkv * rows_per_seq + 32 * cw - 1) / (32 * cw);
   p.scale_log2 = 1.4426950408889634f / sqrtf((float)d);
   p.o_part = scratch;
   p.ml_part = scratch + (size_t)R * H * n_splits * D;
-  hipLaunchKernelGGL(attn_tree_bf16_kernel, dim3(B * p.n_qblocks * n_splits * Hkv), dim3(512), 0, st, p);
-  hipError_t e = hipGetLastError();
+  const int grid = B * p.n_qblocks * n_splits * Hkv;
+  hipError_t e = cw == 1 ? launch_attn_cw<1>(p, grid, st) : cw == 2 ? launch_attn_cw<2>(p, grid, st) : launch_attn_cw<4>(p, grid, st);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_merge_kernel, dim3((R * H * 32 + 255) / 256), dim3(256), 0, st, p.o_part, p.ml_part, R,
                      rows_per_seq, H, n_splits, (bf16_t*)out);

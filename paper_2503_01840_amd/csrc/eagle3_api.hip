@@ -65,7 +65,7 @@ struct eagle3_ctx {
   float* x; void* act_k; void* act_attn; void* act_h; void* q; float* part; float* attn_scratch;
   int32_t* depth; uint32_t* mask; int32_t* slot; float* cs; SeqInfo* seq;
   float* accept_stats;
-  float* z; float* a_buf; int32_t* pos1; DraftState ds;
+  float* z; float* a_buf; int32_t* pos1; float* topk_scratch; DraftState ds;
 
   void carve(void* base) {
     const eagle3_config& c = cfg;
@@ -88,6 +88,7 @@ struct eagle3_ctx {
     z = cv.take<float>((size_t)Md_max * c.draft_vocab);
     a_buf = cv.take<float>((size_t)a_rows * k);
     pos1 = cv.take<int32_t>(Md_max);
+    topk_scratch = cv.take<float>(topk_scratch_floats(c.max_topk, c.draft_vocab, c.max_topk));
     ds.pool_tok = cv.take<int32_t>(pool_max);
     ds.pool_parent = cv.take<int32_t>(pool_max);
     ds.pool_depth = cv.take<int32_t>(pool_max);
@@ -465,7 +466,7 @@ int eagle3_draft_expand(eagle3_ctx* ctx, const float* g_new, const int32_t* tok_
     GemmWeights Wlm = {{ctx->dw.lm_head, nullptr, nullptr}, {Vd, 0, 0}, 1, 0};
     TRY(ctx->project(ctx->act_k, Wlm, M, Vd, k, GEMM_EPI_PARTIAL, nullptr, st, ctx->z));
     const int row0 = level == 1 ? n_new - 1 : 0, n_rows = level == 1 ? 1 : K;
-    CK(launch_topk_rows(ctx->z, Vd, row0, n_rows, Vd, K, ds.top_val, ds.top_idx, st));
+    CK(launch_topk_rows(ctx->z, Vd, row0, n_rows, Vd, K, ctx->topk_scratch, ds.top_val, ds.top_idx, st));
     CK(launch_draft_select(ds, ctx->dw.d2t, dkv->kv_indptr, dkv->prefix_len, level, depth, K, n_new, 0, st));
   }
   CK(launch_draft_rerank(ds, ctx->dw.d2t, tok_new, n_new, depth, K, n_nodes, tree_tok, parent, node_depth, cum_logprob,

@@ -176,31 +176,44 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
   }
 }
 
+// One workgroup per row, four consecutive columns per thread and pass, the row kept in registers between the
+// sum-of-squares pass and the normalising pass (k <= 4 * 4 * blockDim.x).
 template <bool BF16>
-__global__ __launch_bounds__(256) void draft_input_kernel(const typename Act<BF16>::type* __restrict__ embed, int vocab,
-                                                         const int32_t* __restrict__ tok, const float* __restrict__ feat,
-                                                         const int32_t* __restrict__ src_row, int k,
-                                                         const typename Act<BF16>::type* __restrict__ g_embed,
-                                                         const typename Act<BF16>::type* __restrict__ g_feat, float eps,
-                                                         typename Act<BF16>::type* __restrict__ act,
-                                                         float* __restrict__ y) {
-  __shared__ float red[17];
+__global__ __launch_bounds__(1024) void draft_input_kernel(const typename Act<BF16>::type* __restrict__ embed, int vocab,
+                                                          const int32_t* __restrict__ tok, const float* __restrict__ feat,
+                                                          const int32_t* __restrict__ src_row, int k,
+                                                          const typename Act<BF16>::type* __restrict__ g_embed,
+                                                          const typename Act<BF16>::type* __restrict__ g_feat, float eps,
+                                                          typename Act<BF16>::type* __restrict__ act,
+                                                          float* __restrict__ y) {
+  __shared__ float red_e[17], red_f[17];
   const int r = blockIdx.x;
   const int t = min(max(tok[r], 0), vocab - 1);
   const float* f = feat + (size_t)(src_row ? src_row[r] : r) * k;
+  float4 e[4], v[4];
   float se = 0.f, sf = 0.f;
-  for (int c = threadIdx.x; c < k; c += 256) {
-    const float e = load_f32(embed, (size_t)t * k + c), v = f[c];
-    y[(size_t)r * k + c] = v;
-    se += e * e;
-    sf += v * v;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int c = 4 * (threadIdx.x + j * blockDim.x);
+    if (c < k) {
+      e[j] = load4_f32(embed, (size_t)t * k + c);
+      v[j] = *(const float4*)(f + c);
+      *(float4*)(y + (size_t)r * k + c) = v[j];
+      se += e[j].x * e[j].x + e[j].y * e[j].y + e[j].z * e[j].z + e[j].w * e[j].w;
+      sf += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
+    }
   }
-  se = block_sum(se, red);
-  sf = block_sum(sf, red);
+  se = block_sum(se, red_e);
+  sf = block_sum(sf, red_f);
   const float ie = 1.0f / sqrtf(se / (float)k + eps), iv = 1.0f / sqrtf(sf / (float)k + eps);
-  for (int c = threadIdx.x; c < k; c += 256) {
-    Act<BF16>::store(act, r, c, 2 * k, load_f32(embed, (size_t)t * k + c) * ie * load_f32(g_embed, c));
-    Act<BF16>::store(act, r, k + c, 2 * k, f[c] * iv * load_f32(g_feat, c));
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int c = 4 * (threadIdx.x + j * blockDim.x);
+    if (c < k) {
+      const float4 ge = load4_f32(g_embed, c), gf = load4_f32(g_feat, c);
+      Act<BF16>::store4(act, r, c, 2 * k, e[j].x * ie * ge.x, e[j].y * ie * ge.y, e[j].z * ie * ge.z, e[j].w * ie * ge.w);
+      Act<BF16>::store4(act, r, k + c, 2 * k, v[j].x * iv * gf.x, v[j].y * iv * gf.y, v[j].z * iv * gf.z, v[j].w * iv * gf.w);
+    }
   }
 }
 
@@ -300,12 +313,14 @@ hipError_t launch_reduce_partials(const float* partial, int S, int M, int N, flo
 hipError_t launch_draft_input(bool bf16, const void* embed, int vocab, const int32_t* tok, const float* feat,
                               const int32_t* src_row, int M, int k, const void* g_embed, const void* g_feat, float eps,
                               void* act, float* y, hipStream_t st) {
+  if (k % 4 || k > 16384) return hipErrorInvalidValue;
+  const int threads = std::min(1024, ((k / 4 + 63) / 64) * 64);
   if (bf16)
-    hipLaunchKernelGGL(draft_input_kernel<true>, dim3(M), dim3(256), 0, st, (const bf16_t*)embed, vocab, tok, feat, src_row,
-                       k, (const bf16_t*)g_embed, (const bf16_t*)g_feat, eps, (bf16_t*)act, y);
+    hipLaunchKernelGGL(draft_input_kernel<true>, dim3(M), dim3(threads), 0, st, (const bf16_t*)embed, vocab, tok, feat,
+                       src_row, k, (const bf16_t*)g_embed, (const bf16_t*)g_feat, eps, (bf16_t*)act, y);
   else
-    hipLaunchKernelGGL(draft_input_kernel<false>, dim3(M), dim3(256), 0, st, (const float*)embed, vocab, tok, feat, src_row,
-                       k, (const float*)g_embed, (const float*)g_feat, eps, (float*)act, y);
+    hipLaunchKernelGGL(draft_input_kernel<false>, dim3(M), dim3(threads), 0, st, (const float*)embed, vocab, tok, feat,
+                       src_row, k, (const float*)g_embed, (const float*)g_feat, eps, (float*)act, y);
   return hipGetLastError();
 }
 

@@ -101,8 +101,10 @@ struct DraftState {          // device arrays owned by the workspace
   SeqInfo* seq;              // [1]
 };
 // Per-row log-softmax normaliser and top-K (value desc, id asc) over z[row, 0..V).
-hipError_t launch_topk_rows(const float* z, int ld, int row0, int n_rows, int V, int K, float* top_val, int32_t* top_idx,
-                            hipStream_t st);
+// scratch: topk_scratch_floats(n_rows, V, K) floats.
+size_t topk_scratch_floats(int n_rows, int V, int K);
+hipError_t launch_topk_rows(const float* z, int ld, int row0, int n_rows, int V, int K, float* scratch, float* top_val,
+                            int32_t* top_idx, hipStream_t st);
 // Level bookkeeping after forward `level` (1-based): writes the new pool entries and, when level < depth,
 // picks the next frontier and the next forward's row inputs.
 hipError_t launch_draft_select(const DraftState& s, const int32_t* d2t, const int32_t* kv_indptr, const int32_t* prefix_len,

@@ -40,73 +40,88 @@ __device__ __forceinline__ ValIdx block_best(ValIdx x, ValIdx* red) {
   return red[16];
 }
 
-// Row top-K with the row held in registers (V <= 1024 * EPT): every thread keeps the best of its own
-// entries; each of the K rounds is one block-wide arg-max, after which only the winning thread rescans.
-template <int EPT>
-__global__ __launch_bounds__(1024) void topk_rows_kernel(const float* __restrict__ z, int ld, int row0, int V, int K,
-                                                        float* __restrict__ top_val, int32_t* __restrict__ top_idx) {
-  __shared__ float red[17];
-  __shared__ ValIdx redv[17];
-  const float* zr = z + (size_t)(row0 + blockIdx.x) * ld;
-  const int tid = threadIdx.x;
-  float v[EPT];
+// Row top-K in two levels, no workgroup barrier anywhere.
+// Level 1: one wavefront per 512 consecutive logits (8 per lane, held in registers) finds its own top K by K
+// rounds of a wavefront arg-max, and the (max, sum of exp) of its span.
+constexpr int TOPK_SPAN = 512;
+__global__ __launch_bounds__(256) void topk_spans_kernel(const float* __restrict__ z, int ld, int row0, int V, int K,
+                                                        int n_spans, float* __restrict__ cand_val,
+                                                        int32_t* __restrict__ cand_idx, float* __restrict__ span_stat) {
+  const int lane = threadIdx.x & 63, span = blockIdx.x * 4 + (threadIdx.x >> 6), row = blockIdx.y;
+  if (span >= n_spans) return;
+  const float* zr = z + (size_t)(row0 + row) * ld;
+  const int base = span * TOPK_SPAN;
+  float v[8];
   float mx = -INFINITY;
 #pragma unroll
-  for (int j = 0; j < EPT; ++j) {
-    const int c = tid + j * 1024;
+  for (int j = 0; j < 8; ++j) {
+    const int c = base + j * 64 + lane;
     v[j] = c < V ? zr[c] : -INFINITY;
     mx = fmaxf(mx, v[j]);
   }
-  mx = block_max(mx, red);
+  mx = wave_max(mx);                                   // base < V, so at least one entry is finite
   float sum = 0.f;
 #pragma unroll
-  for (int j = 0; j < EPT; ++j) sum += expf(v[j] - mx);          // exp(-inf) = 0 for the padding
-  sum = block_sum(sum, red);
-  const float lse = logf(sum);
+  for (int j = 0; j < 8; ++j) sum += expf(v[j] - mx);  // exp(-inf) = 0 for the padding
+  sum = wave_sum(sum);
+  const size_t o = (size_t)row * n_spans + span;
+  if (lane == 0) { span_stat[2 * o] = mx; span_stat[2 * o + 1] = sum; }
   for (int r = 0; r < K; ++r) {
     ValIdx b = {-INFINITY, INT_MAX};
 #pragma unroll
-    for (int j = 0; j < EPT; ++j)
-      if (v[j] > b.v) { b.v = v[j]; b.i = tid + j * 1024; }      // ascending index per thread: first maximum kept
-    b = block_best(b, redv);
-    if (tid == 0) {
-      top_val[blockIdx.x * K + r] = b.v - mx - lse;
-      top_idx[blockIdx.x * K + r] = b.i;
-    }
-    if ((b.i & 1023) == tid) {
+    for (int j = 0; j < 8; ++j)
+      if (v[j] > b.v) { b.v = v[j]; b.i = base + j * 64 + lane; }   // ascending index per lane: first maximum kept
+    b = wave_best(b);
+    if (lane == 0) { cand_val[o * K + r] = b.v; cand_idx[o * K + r] = b.i; }
 #pragma unroll
-      for (int j = 0; j < EPT; ++j)
-        if (j == (b.i >> 10)) v[j] = -INFINITY;
-    }
+    for (int j = 0; j < 8; ++j)
+      if (b.i == base + j * 64 + lane) v[j] = -INFINITY;
   }
 }
 
-// Any V: K passes over the row in global memory.
-__global__ __launch_bounds__(1024) void topk_rows_big_kernel(const float* __restrict__ z, int ld, int row0, int V, int K,
-                                                            float* __restrict__ top_val, int32_t* __restrict__ top_idx) {
-  __shared__ float red[17];
-  __shared__ ValIdx redv[17];
-  const float* zr = z + (size_t)(row0 + blockIdx.x) * ld;
-  const int tid = threadIdx.x;
+// Level 2: one wavefront per row merges the spans' candidates (K rounds of arg-max over n_spans K entries, each
+// round restricted to entries after the previous pick in the (value desc, index asc) order) and their statistics
+// into the log-softmax normaliser.
+__global__ __launch_bounds__(64) void topk_merge_kernel(const float* __restrict__ cand_val, const int32_t* __restrict__ cand_idx,
+                                                       const float* __restrict__ span_stat, int n_spans, int K,
+                                                       float* __restrict__ top_val, int32_t* __restrict__ top_idx) {
+  const int lane = threadIdx.x, row = blockIdx.x;
+  const float* st = span_stat + (size_t)row * n_spans * 2;
   float mx = -INFINITY;
-  for (int c = tid; c < V; c += 1024) mx = fmaxf(mx, zr[c]);
-  mx = block_max(mx, red);
+  for (int i = lane; i < n_spans; i += 64) mx = fmaxf(mx, st[2 * i]);
+  mx = wave_max(mx);
   float sum = 0.f;
-  for (int c = tid; c < V; c += 1024) sum += expf(zr[c] - mx);
-  sum = block_sum(sum, red);
+  for (int i = lane; i < n_spans; i += 64) sum += st[2 * i + 1] * expf(st[2 * i] - mx);
+  sum = wave_sum(sum);
   const float lse = logf(sum);
+  const int C = n_spans * K;
+  const float* cv = cand_val + (size_t)row * C;
+  const int32_t* ci = cand_idx + (size_t)row * C;
+  constexpr int CPL = 16;                              // candidates per lane kept in registers
+  float v[CPL];
+  int id[CPL];
+#pragma unroll
+  for (int j = 0; j < CPL; ++j) {
+    const int c = j * 64 + lane;
+    v[j] = c < C ? cv[c] : -INFINITY;
+    id[j] = c < C ? ci[c] : INT_MAX;
+  }
   float pv = INFINITY;
   int pi = -1;
   for (int r = 0; r < K; ++r) {
     ValIdx b = {-INFINITY, INT_MAX};
-    for (int c = tid; c < V; c += 1024) {
-      const float v = zr[c];
-      if ((v < pv || (v == pv && c > pi)) && better(v, c, b.v, b.i)) { b.v = v; b.i = c; }
+#pragma unroll
+    for (int j = 0; j < CPL; ++j)
+      if ((v[j] < pv || (v[j] == pv && id[j] > pi)) && better(v[j], id[j], b.v, b.i)) { b.v = v[j]; b.i = id[j]; }
+    for (int c = CPL * 64 + lane; c < C; c += 64) {    // more candidates than the registers hold: from memory
+      const float x = cv[c];
+      const int xi = ci[c];
+      if ((x < pv || (x == pv && xi > pi)) && better(x, xi, b.v, b.i)) { b.v = x; b.i = xi; }
     }
-    b = block_best(b, redv);
-    if (tid == 0) {
-      top_val[blockIdx.x * K + r] = b.v - mx - lse;
-      top_idx[blockIdx.x * K + r] = b.i;
+    b = wave_best(b);
+    if (lane == 0) {
+      top_val[row * K + r] = b.v - mx - lse;
+      top_idx[row * K + r] = b.i;
     }
     pv = b.v;
     pi = b.i;
@@ -231,14 +246,24 @@ __global__ __launch_bounds__(1024) void draft_rerank_kernel(DraftState s, const 
 
 }  // namespace
 
-hipError_t launch_topk_rows(const float* z, int ld, int row0, int n_rows, int V, int K, float* top_val, int32_t* top_idx,
-                            hipStream_t st) {
-  if (V <= 8 * 1024)
-    hipLaunchKernelGGL(topk_rows_kernel<8>, dim3(n_rows), dim3(1024), 0, st, z, ld, row0, V, K, top_val, top_idx);
-  else if (V <= 32 * 1024)
-    hipLaunchKernelGGL(topk_rows_kernel<32>, dim3(n_rows), dim3(1024), 0, st, z, ld, row0, V, K, top_val, top_idx);
-  else
-    hipLaunchKernelGGL(topk_rows_big_kernel, dim3(n_rows), dim3(1024), 0, st, z, ld, row0, V, K, top_val, top_idx);
+size_t topk_scratch_floats(int n_rows, int V, int K) {
+  const size_t n_spans = (size_t)(V + TOPK_SPAN - 1) / TOPK_SPAN;
+  return (size_t)n_rows * n_spans * (2 * (size_t)K + 2);
+}
+
+hipError_t launch_topk_rows(const float* z, int ld, int row0, int n_rows, int V, int K, float* scratch, float* top_val,
+                            int32_t* top_idx, hipStream_t st) {
+  if (n_rows <= 0 || V <= 0 || K <= 0) return hipErrorInvalidValue;
+  const int n_spans = (V + TOPK_SPAN - 1) / TOPK_SPAN;
+  float* cand_val = scratch;
+  int32_t* cand_idx = (int32_t*)(scratch + (size_t)n_rows * n_spans * K);
+  float* span_stat = scratch + 2 * (size_t)n_rows * n_spans * K;
+  hipLaunchKernelGGL(topk_spans_kernel, dim3((n_spans + 3) / 4, n_rows), dim3(256), 0, st, z, ld, row0, V, K, n_spans,
+                     cand_val, cand_idx, span_stat);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(topk_merge_kernel, dim3(n_rows), dim3(64), 0, st, cand_val, cand_idx, span_stat, n_spans, K, top_val,
+                     top_idx);
   return hipGetLastError();
 }
 

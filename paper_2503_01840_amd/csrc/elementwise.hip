@@ -76,8 +76,21 @@ __global__ __launch_bounds__(256) void tree_prep_kernel(const int32_t* __restric
                                                        int32_t* __restrict__ slot, float* __restrict__ cs,
                                                        SeqInfo* __restrict__ seq) {
   __shared__ int sdepth[64];
-  const int b = blockIdx.x, i = threadIdx.x;
+  __shared__ int rank;
+  const int b = blockIdx.x, i = threadIdx.x, B = gridDim.x;
   const int P = prefix_len[b], base = kv_indptr[b];
+  // rank of this sequence by prefix length, longest first (ties: smaller index first): attention hands out its
+  // workgroups in that order, so that the long sequences start first and the short ones fill the tail
+  if (i == 0) rank = 0;
+  __syncthreads();
+  int longer = 0;
+  for (int o = i; o < B; o += 256) {
+    const int Po = prefix_len[o];
+    longer += (Po > P || (Po == P && o < b)) ? 1 : 0;
+  }
+  if (longer) atomicAdd(&rank, longer);
+  __syncthreads();
+  if (i == 0) seq[rank].order = b;
   if (i < N) {
     uint32_t m[4] = {0u, 0u, 0u, 0u};
     int cur = i, dep = 0;
@@ -95,7 +108,7 @@ __global__ __launch_bounds__(256) void tree_prep_kernel(const int32_t* __restric
 #pragma unroll
     for (int w = 0; w < 4; ++w) mask[r * 4 + w] = m[w];
   }
-  if (i == 0) { seq[b].kv_base = base; seq[b].n_prefix = P; seq[b].n_tail = N; seq[b].pad = 0; }
+  if (i == 0) { seq[b].kv_base = base; seq[b].n_prefix = P; seq[b].n_tail = N; }
   __syncthreads();
   const int half = d / 2;
   for (int e = i; e < N * half; e += 256) {
@@ -231,7 +244,7 @@ __global__ __launch_bounds__(64) void draft_prep1_kernel(const int32_t* __restri
       mask[j * 4 + w] = j < lo ? 0u : (j - lo >= 31 ? 0xFFFFFFFFu : ((2u << (j - lo)) - 1u));
     }
   }
-  if (j == 0) { seq[0].kv_base = base; seq[0].n_prefix = P; seq[0].n_tail = n_new; seq[0].pad = 0; }
+  if (j == 0) { seq[0].kv_base = base; seq[0].n_prefix = P; seq[0].n_tail = n_new; seq[0].order = 0; }
 }
 
 }  // namespace

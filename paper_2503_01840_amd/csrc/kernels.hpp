@@ -42,7 +42,7 @@ struct SeqInfo {           // one per sequence, device resident
   int32_t kv_base;         // first cache slot of the sequence
   int32_t n_prefix;        // slots visible to every row
   int32_t n_tail;          // following slots, visible according to the per-row bit mask
-  int32_t pad;
+  int32_t order;           // entry i: the sequence that attention workgroup group i works on (longest first)
 };
 
 hipError_t launch_embed_rows(bool bf16, const void* embed, const int32_t* tok, int R, int k, int vocab, float* x,

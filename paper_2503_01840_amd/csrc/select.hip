@@ -184,7 +184,7 @@ __global__ __launch_bounds__(256) void draft_select_kernel(DraftState s, const i
       s.seq[0].kv_base = kv_indptr[0];
       s.seq[0].n_prefix = P + n_new;
       s.seq[0].n_tail = level * K;
-      s.seq[0].pad = 0;
+      s.seq[0].order = 0;
     }
   }
 }

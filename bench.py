@@ -6,7 +6,11 @@ expansion (depth D, top-K, N-node tree), tree-masked verification through every 
 LM head, and the acceptance walk (greedy and temperature 1).  Inputs (random-init LLaMA-shaped weights,
 random KV caches) are resident in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3] [--no-cpu-baseline] [--calibrate-copy]
+
+--config c4 times the batched case instead (64 ragged sequences x 8-node trees: verification + acceptance, no
+drafting) and prices its GEMMs against the MFMA peak.  --calibrate-copy appends three plain 256 MiB device copies
+after the run, the reference that hardware-counter runs (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) are scaled by.
 """
 import argparse
 import json
@@ -19,6 +23,8 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = 2500.0       # MI355X dense bf16, published
+COPY_BYTES = 256 << 20
 
 
 def algorithmic_bytes(shape, n_new):
@@ -39,7 +45,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="c3", choices=["c2", "c3", "c5"])
+    ap.add_argument("--config", default="c3", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--calibrate-copy", action="store_true")
     ap.add_argument("--n-new", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -54,6 +61,12 @@ def main():
     shape = S.get_shape(args.config)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.config == "c4":
+        out = bench_batched(args, shape, torch, S, E, dev)
+        if args.calibrate_copy:
+            calibrate_copy(torch, dev)
+        print(json.dumps(out))
+        return
     P, N, D, K, n_new = shape.prefix_lo, shape.n_nodes, shape.depth, shape.topk, args.n_new
     ctx = E.Eagle3Context(shape, max_batch=1, max_nodes=64, max_depth=D, max_topk=K, max_new=max(8, n_new), device=dev)
     T = S.TensorIds
@@ -120,7 +133,7 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": "gemm_skinny_kernel<2> (verification GEMMs, 60 activation rows)",
         "achieved": g_bytes / g_ms / 1e6, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-        "frac": g_bytes / g_ms / 1e6 / HBM_PEAK_GBPS, "traffic": None,
+        "frac": g_bytes / g_ms / 1e6 / HBM_PEAK_GBPS, "traffic": stored_traffic(args.config),
         "launches_per_step": g_n, "avg_launch_us": g_ms / g_n * 1e3, "bytes_per_launch": g_bytes / g_n,
         "draft_gemm_GBps": d_bytes / d_ms / 1e6 if d_ms else None,
         "step_algorithmic_GB": ab["step"] / 1e9, "step_GBps": ab["step"] / ms_per_step / 1e6,
@@ -128,7 +141,7 @@ def main():
     }
 
     out = {
-        "metric": "tree tokens verified/s over the whole draft+verify step (8B-shape bs1)",
+        "metric": "tree tokens verified/s over the whole draft+verify step (%s-shape bs1)" % ("70B" if args.config == "c5" else "8B"),
         "value": N / ms_per_step * 1e3, "unit": "tree tokens verified/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "step_us": ms_per_step * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
@@ -144,7 +157,98 @@ def main():
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape)
+    if args.calibrate_copy:
+        calibrate_copy(torch, dev)
     print(json.dumps(out))
+
+
+def calibrate_copy(torch, dev):
+    """Three plain device-to-device copies of COPY_BYTES: what a counter run reads for them is the scale for
+    the counters of every other dispatch."""
+    a = torch.empty(COPY_BYTES // 4, dtype=torch.float32, device=dev).normal_()
+    b = torch.empty_like(a)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        b.copy_(a)
+    torch.cuda.synchronize()
+
+
+def stored_traffic(config):
+    """HBM bytes per launch of the dominant kernel from the committed hardware-counter summary (rocprofv3 --pmc
+    runs of this script are separate invocations: their result is a stored figure, or null)."""
+    path = os.path.join(ROOT, "profiles", f"{config}_gemm_pmc_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def bench_batched(args, shape, torch, S, E, dev):
+    """c4: 64 ragged sequences, 8-node trees: one tree_verify + greedy and T=1 acceptance per step."""
+    rb = S.ragged_batch(shape)
+    B, N = shape.batch, shape.n_nodes
+    ctx = E.Eagle3Context(shape, max_batch=B, max_nodes=N, max_depth=shape.depth, max_topk=shape.topk, max_new=8, device=dev)
+    tg = S.target_globals(shape, device=dev)
+    ctx.set_weights({"layers": [S.layer_weights(shape, l, device=dev) for l in range(shape.n_layers)], **tg}, None)
+    total = int(rb["kv_indptr"][-1])
+    ks, vs = zip(*[S.kv_layer(shape, l, total, device=dev) for l in range(shape.n_layers)])
+    kv = E.KVCache(ks, vs, torch.as_tensor(rb["kv_indptr"], device=dev), torch.as_tensor(rb["prefix_len"], device=dev),
+                   int(rb["prefix_len"].max()))
+    tt, pp = torch.as_tensor(rb["tree_tok"], device=dev), torch.as_tensor(rb["parent"], device=dev)
+    logits = torch.empty(B, N, shape.vocab, device=dev)
+    taps = torch.empty(3, B, N, shape.hidden, device=dev)
+    U = S.uniform01(S.SEED, S.TensorIds.UNIFORMS, (B, 2 * N), device=dev)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+    def step(record=False):
+        if record: ev[0].record()
+        E.eagle3_tree_verify(ctx, tt, pp, kv, logits=logits, taps=taps)
+        if record: ev[1].record()
+        E.eagle3_accept(ctx, logits, tt, pp, 0.0)
+        E.eagle3_accept(ctx, logits, tt, pp, 1.0, U)
+        if record: ev[2].record()
+
+    steps = min(args.steps, 10)
+    for _ in range(min(args.warmup, 3)):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / steps * 1e3
+    step(record=True)
+    torch.cuda.synchronize()
+    verify_ms, accept_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
+    ctx.profile_begin()
+    step()
+    torch.cuda.synchronize()
+    g_ms, g_n, g_bytes = ctx.profile_read(1)
+    ctx.profile_end()
+    R = B * N
+    flops = g_bytes * R                      # 2 N K bytes per launch -> 2 R N K FLOP
+    kv_bytes = 2 * total * shape.kv_dim * 2 * shape.n_layers
+    return {
+        "metric": "tree tokens verified/s over verification + acceptance (8B-shape bs64)",
+        "value": R / ms_per_step * 1e3, "unit": "tree tokens verified/s", "n_gpus": 1, "steps": steps,
+        "warmup": min(args.warmup, 3), "ms_per_step": ms_per_step, "step_us": ms_per_step * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"c4: {shape.n_layers}-layer LLaMA-8B-shaped tree verification + acceptance, {B} sequences with "
+                               f"{int(rb['prefix_len'].min())}..{int(rb['prefix_len'].max())}-token caches (ragged), {N}-node trees",
+                   "parallelism": "single GPU"},
+        "call_us": {"tree_verify": verify_ms * 1e3, "accept_greedy_plus_stochastic": accept_ms * 1e3},
+        "roofline": {
+            "bound": "mfma", "kernel": "gemm_wide_kernel (verification GEMMs, 512 activation rows)",
+            "achieved": flops / g_ms / 1e9, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": flops / g_ms / 1e9 / MFMA_PEAK_TFLOPS, "traffic": None,
+            "launches_per_step": g_n, "avg_launch_us": g_ms / g_n * 1e3, "flop_per_launch": flops / g_n,
+            "gemm_ms_per_step": g_ms, "verify_flop_over_verify_time_frac": flops / verify_ms / 1e9 / MFMA_PEAK_TFLOPS,
+            "kv_cache_GB_per_step": kv_bytes / 1e9, "weights_GB_per_step": g_bytes / 1e9,
+        },
+    }
 
 
 def cpu_baseline(shape, n_layers=8):

@@ -170,7 +170,7 @@ int eagle3_create(const eagle3_config* cfg, eagle3_ctx** out) {
   if (!cfg || !out) return EAGLE3_E_NULL;
   const eagle3_config& c = *cfg;
   if (c.hidden <= 0 || c.n_heads <= 0 || c.n_kv_heads <= 0 || c.head_dim <= 0 || c.intermediate <= 0 || c.vocab <= 0 ||
-      c.draft_vocab <= 0 || c.n_layers <= 0 || c.n_heads % c.n_kv_heads != 0)
+      c.draft_vocab <= 0 || c.draft_vocab > 512 * 1024 || c.n_layers <= 0 || c.n_heads % c.n_kv_heads != 0)
     return EAGLE3_E_SHAPE;
   if (c.dtype != EAGLE3_BF16 && c.dtype != EAGLE3_FP32) return EAGLE3_E_SHAPE;
   if (c.max_batch < 1 || c.max_nodes < 1 || c.max_nodes > 64 || c.max_depth < 1 || c.max_topk < 1 || c.max_topk > 16 ||

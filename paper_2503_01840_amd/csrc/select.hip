@@ -79,12 +79,21 @@ __global__ __launch_bounds__(256) void topk_spans_kernel(const float* __restrict
   }
 }
 
-// Level 2: one wavefront per row merges the spans' candidates (K rounds of arg-max over n_spans K entries, each
-// round restricted to entries after the previous pick in the (value desc, index asc) order) and their statistics
-// into the log-softmax normaliser.
+// Level 2: one wavefront per row merges the spans' candidates and statistics, without sequential selection rounds.
+// In the order (value desc, index asc) the K-th best of the spans' BEST candidates bounds the answer from below:
+// at least K candidates are not worse than it, so only candidates not worse than it can be among the top K, and
+// those come from exactly K spans (at most K * K survivors).  The survivors are ranked by counting, and rank r < K
+// is output r.
+constexpr int TOPK_MAX_SPANS = 1024, TOPK_MAX_K = 16;
 __global__ __launch_bounds__(64) void topk_merge_kernel(const float* __restrict__ cand_val, const int32_t* __restrict__ cand_idx,
                                                        const float* __restrict__ span_stat, int n_spans, int K,
                                                        float* __restrict__ top_val, int32_t* __restrict__ top_idx) {
+  __shared__ float head_v[TOPK_MAX_SPANS];
+  __shared__ int head_i[TOPK_MAX_SPANS];
+  __shared__ float surv_v[TOPK_MAX_K * TOPK_MAX_K];
+  __shared__ int surv_i[TOPK_MAX_K * TOPK_MAX_K];
+  __shared__ float bound_v;
+  __shared__ int bound_i, n_surv;
   const int lane = threadIdx.x, row = blockIdx.x;
   const float* st = span_stat + (size_t)row * n_spans * 2;
   float mx = -INFINITY;
@@ -97,34 +106,42 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(const float* __restrict_
   const int C = n_spans * K;
   const float* cv = cand_val + (size_t)row * C;
   const int32_t* ci = cand_idx + (size_t)row * C;
-  constexpr int CPL = 16;                              // candidates per lane kept in registers
-  float v[CPL];
-  int id[CPL];
-#pragma unroll
-  for (int j = 0; j < CPL; ++j) {
-    const int c = j * 64 + lane;
-    v[j] = c < C ? cv[c] : -INFINITY;
-    id[j] = c < C ? ci[c] : INT_MAX;
+  for (int i = lane; i < n_spans; i += 64) { head_v[i] = cv[i * K]; head_i[i] = ci[i * K]; }
+  if (lane == 0) { n_surv = 0; bound_v = -INFINITY; bound_i = INT_MAX; }      // fewer than K spans: everything survives
+  __syncthreads();
+  const int kth = K - 1;
+  for (int i = lane; i < n_spans; i += 64) {
+    const float v = head_v[i];
+    const int id = head_i[i];
+    int rank = 0;
+    for (int j = 0; j < n_spans; ++j) rank += better(head_v[j], head_i[j], v, id) ? 1 : 0;
+    if (rank == kth) { bound_v = v; bound_i = id; }
   }
-  float pv = INFINITY;
-  int pi = -1;
-  for (int r = 0; r < K; ++r) {
-    ValIdx b = {-INFINITY, INT_MAX};
-#pragma unroll
-    for (int j = 0; j < CPL; ++j)
-      if ((v[j] < pv || (v[j] == pv && id[j] > pi)) && better(v[j], id[j], b.v, b.i)) { b.v = v[j]; b.i = id[j]; }
-    for (int c = CPL * 64 + lane; c < C; c += 64) {    // more candidates than the registers hold: from memory
-      const float x = cv[c];
-      const int xi = ci[c];
-      if ((x < pv || (x == pv && xi > pi)) && better(x, xi, b.v, b.i)) { b.v = x; b.i = xi; }
+  __syncthreads();
+  const float bv = bound_v;
+  const int bi = bound_i;
+  for (int i = lane; i < n_spans; i += 64) {
+    if (better(bv, bi, head_v[i], head_i[i])) continue;                        // the whole span is worse than the bound
+    for (int r = 0; r < K; ++r) {
+      const float v = cv[i * K + r];
+      const int id = ci[i * K + r];
+      if (better(bv, bi, v, id)) break;                                        // a span's candidates are in order
+      const int pos = atomicAdd(&n_surv, 1);
+      surv_v[pos] = v;
+      surv_i[pos] = id;
     }
-    b = wave_best(b);
-    if (lane == 0) {
-      top_val[row * K + r] = b.v - mx - lse;
-      top_idx[row * K + r] = b.i;
+  }
+  __syncthreads();
+  const int T = n_surv;
+  for (int t = lane; t < T; t += 64) {
+    const float v = surv_v[t];
+    const int id = surv_i[t];
+    int rank = 0;
+    for (int j = 0; j < T; ++j) rank += better(surv_v[j], surv_i[j], v, id) ? 1 : 0;
+    if (rank < K) {
+      top_val[row * K + rank] = v - mx - lse;
+      top_idx[row * K + rank] = id;
     }
-    pv = b.v;
-    pi = b.i;
   }
 }
 
@@ -253,8 +270,9 @@ size_t topk_scratch_floats(int n_rows, int V, int K) {
 
 hipError_t launch_topk_rows(const float* z, int ld, int row0, int n_rows, int V, int K, float* scratch, float* top_val,
                             int32_t* top_idx, hipStream_t st) {
-  if (n_rows <= 0 || V <= 0 || K <= 0) return hipErrorInvalidValue;
+  if (n_rows <= 0 || V <= 0 || K <= 0 || K > TOPK_MAX_K) return hipErrorInvalidValue;
   const int n_spans = (V + TOPK_SPAN - 1) / TOPK_SPAN;
+  if (n_spans > TOPK_MAX_SPANS) return hipErrorInvalidValue;
   float* cand_val = scratch;
   int32_t* cand_idx = (int32_t*)(scratch + (size_t)n_rows * n_spans * K);
   float* span_stat = scratch + 2 * (size_t)n_rows * n_spans * K;

@@ -98,16 +98,8 @@ __global__ __launch_bounds__(128 * CW) void attn_tree_bf16_kernel(AttnParams p) 
   const bool wave_active = (qb * CW + cw) * 32 < G * N;
   const int kg = lane >> 5;
 
-  u32x4 qf[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    if (q_valid) qf[ks] = *(const u32x4*)(p.q + ((size_t)row * p.H + head) * D + ks * 16 + kg * 8);
-    else qf[ks] = (u32x4){0u, 0u, 0u, 0u};
-  }
+  u32x4 qf[8];                                 // filled after the first K/V tiles are on their way
   uint32_t mw[4];
-#pragma unroll
-  for (int w = 0; w < 4; ++w) mw[w] = p.mask[(size_t)row * 4 + w];
-  ATTN_WAIT_LOADS(0);                          // from here on the only loads in flight are the direct ones below
 
   const int n_tiles = (L + KT - 1) / KT;
   const int tps = (n_tiles + p.n_splits - 1) / p.n_splits;
@@ -254,6 +246,21 @@ __global__ __launch_bounds__(128 * CW) void attn_tree_bf16_kernel(AttnParams p) 
   // loads in flight" means that my part of tile t has landed; the barrier extends that to every wavefront's part.
 #pragma unroll
   for (int i = 0; i < RD - 1; ++i) issue_tile(t_begin + i);
+  // The query fragments and mask words are ordinary loads issued AFTER those tiles, so that both latencies run
+  // side by side; the compiler's wait for them (at their first use, just below) also covers every direct load
+  // issued so far, and the counted waits in the loop only ever see direct loads younger than that.
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    if (q_valid) qf[ks] = *(const u32x4*)(p.q + ((size_t)row * p.H + head) * D + ks * 16 + kg * 8);
+    else qf[ks] = (u32x4){0u, 0u, 0u, 0u};
+  }
+#pragma unroll
+  for (int w = 0; w < 4; ++w) mw[w] = p.mask[(size_t)row * 4 + w];
+  // consume them here, once: otherwise the compiler re-waits for them inside the loop, which would drain the ring
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) asm volatile("" ::"v"(qf[ks]));
+#pragma unroll
+  for (int w = 0; w < 4; ++w) asm volatile("" ::"v"(mw[w]));
   for (int t = t_begin; t < t_end; ++t) {
     ATTN_WAIT_LOADS((RD - 2) * 2 * IPW);
     __syncthreads();

@@ -15,40 +15,64 @@ namespace {
 
 constexpr int CH = ACCEPT_CHUNK;
 
+// One workgroup per (row, chunk of 2048 logits): the chunk is read once (two 16-byte loads per thread), every
+// wavefront reduces its 512 entries to (max, first arg-max, sum of exp relative to that max) with shuffles, and the
+// four results are combined after a single barrier.
 __global__ __launch_bounds__(256) void accept_stats_kernel(const float* __restrict__ logits, int V, int n_chunks,
                                                           float inv_t, float* __restrict__ stats) {
-  __shared__ float redv[4];
+  __shared__ float redv[4], reds[4];
   __shared__ int redi[4];
-  __shared__ float reds[17];
-  const int c = blockIdx.x, r = blockIdx.y, tid = threadIdx.x;
+  const int c = blockIdx.x, r = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float* z = logits + (size_t)r * V;
-  const int lo = c * CH, hi = min(V, lo + CH);
+  const int lo = c * CH + wave * 512;
+  float x[8];
+  int idx[8];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int v0 = lo + h * 256 + 4 * lane;
+    if (v0 + 3 < V && (V & 3) == 0) {
+      const float4 q = *(const float4*)(z + v0);
+      x[4 * h] = q.x; x[4 * h + 1] = q.y; x[4 * h + 2] = q.z; x[4 * h + 3] = q.w;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) x[4 * h + j] = v0 + j < V ? z[v0 + j] : -INFINITY;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { x[4 * h + j] *= inv_t; idx[4 * h + j] = v0 + j; }
+  }
   float mx = -INFINITY;
   int am = INT_MAX;
-  for (int v = lo + tid; v < hi; v += 256) {
-    const float x = z[v] * inv_t;
-    if (x > mx) { mx = x; am = v; }            // ascending v per thread: first maximum kept
-  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    if (x[j] > mx) { mx = x[j]; am = idx[j]; }   // ascending index per thread: first maximum kept
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     const float ov = __shfl_xor(mx, o, 64);
     const int oi = __shfl_xor(am, o, 64);
     if (ov > mx || (ov == mx && oi < am)) { mx = ov; am = oi; }
   }
-  if ((tid & 63) == 0) { redv[tid >> 6] = mx; redi[tid >> 6] = am; }
-  __syncthreads();
-  mx = redv[0]; am = redi[0];
-#pragma unroll
-  for (int w = 1; w < 4; ++w)
-    if (redv[w] > mx || (redv[w] == mx && redi[w] < am)) { mx = redv[w]; am = redi[w]; }
   float sum = 0.f;
-  for (int v = lo + tid; v < hi; v += 256) sum += expf(z[v] * inv_t - mx);
-  sum = block_sum(sum, reds);
+  if (mx > -INFINITY) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sum += expf(x[j] - mx);   // exp(-inf) = 0 for the padding
+  }
+  sum = wave_sum(sum);
+  if (lane == 0) { redv[wave] = mx; redi[wave] = am; reds[wave] = sum; }
+  __syncthreads();
   if (tid == 0) {
+    float M = redv[0];
+    int A = redi[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w)
+      if (redv[w] > M || (redv[w] == M && redi[w] < A)) { M = redv[w]; A = redi[w]; }
+    float S = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+      if (redv[w] > -INFINITY) S += reds[w] * expf(redv[w] - M);
     float* o = stats + ((size_t)r * n_chunks + c) * 4;
-    o[0] = mx;
-    o[1] = __int_as_float(am);
-    o[2] = sum;
+    o[0] = M;
+    o[1] = __int_as_float(A);
+    o[2] = S;
     o[3] = 0.f;
   }
 }

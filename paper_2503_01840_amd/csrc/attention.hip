@@ -10,8 +10,8 @@
 //     the K/V tiles staged in LDS.  CW is 1, 2 or 4 according to how many such rows there are: many
 //     short-row workgroups (batched verification) pack two to a CU, a single long one fills it;
 //   * K/V tiles of 64 keys reach LDS by direct global-to-LDS loads (1 KiB per wavefront instruction =
-//     four 256-byte cache rows) into a ring of tiles, issued a whole ring ahead: no staging registers, no
-//     LDS store instructions.  Which 16-byte piece of a row a lane fetches is XOR-swizzled with the key
+//     four 256-byte cache rows) into two tile slots, one tile ahead: no staging registers, no LDS store
+//     instructions.  Which 16-byte piece of a row a lane fetches is XOR-swizzled with the key
 //     index so that the operand reads below touch every LDS bank once;
 //   * each wavefront owns 32 query rows and one 32-key block of every tile.  Scores are produced
 //     transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16, so a lane holds 16 keys of ONE query: the
@@ -35,6 +35,7 @@ constexpr int KT = 64;                       // keys per tile = two 32-key score
 constexpr int ROWB = D * 2;                  // bytes per cache row
 constexpr int TILE_BYTES = 2 * KT * ROWB;    // K tile, then V tile
 constexpr float NEG = -1e30f;
+constexpr float MAX_SLACK = 8.f;
 
 struct AttnParams {
   const bf16_t* q;
@@ -64,10 +65,15 @@ __device__ __forceinline__ void pair_values(float x, float& a, float& b) {
 __device__ __forceinline__ void dma16(const void* src, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory", "m0");
 }
+// Same, with the address given as a wavefront-uniform base plus a 32-bit byte offset per lane.
+__device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(lane_off), "s"(base)
+               : "memory", "m0");
+}
 #pragma clang diagnostic pop
 #define ATTN_WAIT_LOADS(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
 
-constexpr int attn_ring(int CW) { return CW == 4 ? 4 : 2; }
+constexpr int RD = 2;                        // tiles in LDS: the one being worked on and the next one arriving
 
 // 2 CW wavefronts.  Wavefront w works on query rows 32 (w >> 1) .. +31 and on key block sb = w & 1 (32 of the 64
 // keys) of every tile, with its own running max / sum / output: the serial chain per tile (8 score MFMAs,
@@ -75,7 +81,7 @@ constexpr int attn_ring(int CW) { return CW == 4 ? 4 : 2; }
 // LDS at the end.
 template <int CW>
 __global__ __launch_bounds__(128 * CW) void attn_tree_bf16_kernel(AttnParams p) {
-  constexpr int NW = 2 * CW, RD = attn_ring(CW);
+  constexpr int NW = 2 * CW;
   constexpr int IPW = 16 / NW;                 // direct loads per wavefront per tile, for K and again for V
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -104,32 +110,48 @@ __global__ __launch_bounds__(128 * CW) void attn_tree_bf16_kernel(AttnParams p) 
   const int n_tiles = (L + KT - 1) / KT;
   const int tps = (n_tiles + p.n_splits - 1) / p.n_splits;
   const int t_begin = split * tps, t_end = min(n_tiles, t_begin + tps);
-  const int t_last = max(t_end - 1, 0);
 
   // Direct loads.  Instruction j (0..15) of a tile brings keys 4j .. 4j+3; lane l fetches, for key 4j + (l >> 4),
   // the piece that belongs at position l & 15 of the swizzled row: K rows hold piece c at position c ^ (key & 15),
-  // V rows hold piece c at position c ^ ((key & 3) << 2).  Keys past the end of the sequence are clamped to its
-  // last key (masked later); tiles past the end of the split repeat its last tile into a slot nobody reads.
+  // V rows hold piece c at position c ^ ((key & 3) << 2).  A tile that lies wholly inside the sequence is fetched
+  // from a wavefront-uniform tile base plus per-lane byte offsets that never change; in the sequence's last tile
+  // keys past the end are clamped to its last key (masked later).
   const size_t row_stride = (size_t)p.Hkv * D;                        // elements between consecutive cache slots
   const bf16_t* kbase = p.kc + ((size_t)si.kv_base * p.Hkv + g) * D;
   const bf16_t* vbase = p.vc + ((size_t)si.kv_base * p.Hkv + g) * D;
   const int lkey = lane >> 4;
   const int vpiece = (lane & 15) ^ ((lkey & 3) << 2);
+  uint32_t koff[IPW], voff[IPW];
+#pragma unroll
+  for (int i = 0; i < IPW; ++i) {
+    const int j = wave * IPW + i;
+    const uint32_t key_bytes = (uint32_t)(4 * j + lkey) * (uint32_t)(row_stride * 2);
+    koff[i] = key_bytes + (uint32_t)(((lane & 15) ^ (4 * (j & 3) + lkey)) * 16);
+    voff[i] = key_bytes + (uint32_t)(vpiece * 16);
+  }
   auto issue_tile = [&](int t) {
-    const int tt = min(t, t_last);
     const uint32_t slot = lds0 + ((t - t_begin) % RD) * TILE_BYTES;
+    if ((t + 1) * KT <= L) {
+      const bf16_t* kt0 = kbase + (size_t)t * KT * row_stride;
+      const bf16_t* vt0 = vbase + (size_t)t * KT * row_stride;
 #pragma unroll
-    for (int i = 0; i < IPW; ++i) {
-      const int j = wave * IPW + i;
-      const int key = max(min(tt * KT + 4 * j + lkey, L - 1), 0);
-      const int kpiece = (lane & 15) ^ (4 * (j & 3) + lkey);
-      dma16(kbase + (size_t)key * row_stride + kpiece * 8, slot + j * 1024);
-    }
+      for (int i = 0; i < IPW; ++i) dma16(kt0, koff[i], slot + (wave * IPW + i) * 1024);
 #pragma unroll
-    for (int i = 0; i < IPW; ++i) {
-      const int j = wave * IPW + i;
-      const int key = max(min(tt * KT + 4 * j + lkey, L - 1), 0);
-      dma16(vbase + (size_t)key * row_stride + vpiece * 8, slot + KT * ROWB + j * 1024);
+      for (int i = 0; i < IPW; ++i) dma16(vt0, voff[i], slot + KT * ROWB + (wave * IPW + i) * 1024);
+    } else {
+#pragma unroll
+      for (int i = 0; i < IPW; ++i) {
+        const int j = wave * IPW + i;
+        const int key = max(min(t * KT + 4 * j + lkey, L - 1), 0);
+        const int kpiece = (lane & 15) ^ (4 * (j & 3) + lkey);
+        dma16(kbase + (size_t)key * row_stride + kpiece * 8, slot + j * 1024);
+      }
+#pragma unroll
+      for (int i = 0; i < IPW; ++i) {
+        const int j = wave * IPW + i;
+        const int key = max(min(t * KT + 4 * j + lkey, L - 1), 0);
+        dma16(vbase + (size_t)key * row_stride + vpiece * 8, slot + KT * ROWB + j * 1024);
+      }
     }
   };
 
@@ -144,6 +166,11 @@ __global__ __launch_bounds__(128 * CW) void attn_tree_bf16_kernel(AttnParams p) 
   const int vcol = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);         // piece within the 32-wide head-dim block
   const int v_half = (lane & 1) * 8;
 
+  // bf16 pairs (-1, 0) and (0, -1), kept in registers: written as literals the compiler folds them into an
+  // inline constant whose two halves the instruction does not read that way
+  uint32_t minus_lo = 0x0000BF80u, minus_hi = 0xBF800000u;
+  asm volatile("" : "+v"(minus_lo), "+v"(minus_hi));
+
   floatx16 o[4];
 #pragma unroll
   for (int db = 0; db < 4; ++db)
@@ -151,19 +178,27 @@ __global__ __launch_bounds__(128 * CW) void attn_tree_bf16_kernel(AttnParams p) 
     for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
   float m_run = NEG, l_run = 0.f;
 
-  auto compute_tile = [&](int t) {
+  // scores and softmax of tile t: updates the running max / sum, rescales the output, leaves exp(S^T) as bf16
+  // head (ph) and tail (pl) operands
+  auto score_tile = [&](int t, u32x4 (&ph)[2], u32x4 (&pl)[2]) {
     const unsigned char* kt = smem + ((t - t_begin) % RD) * TILE_BYTES;
-    const unsigned char* vt = kt + KT * ROWB;
     // S^T = K Q^T for this wavefront's 32-key block, as two interleaved chains over the head dimension
-    floatx16 s, s2;
+    floatx16 s;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { s[r] = 0.f; s2[r] = 0.f; }
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+    {
+      floatx16 s2;
 #pragma unroll
-    for (int ks = 0; ks < 8; ks += 2) {
-      const u32x4 a0 = *(const u32x4*)(kt + k_off + (((2 * ks + kg) ^ k_swz) * 16));
-      const u32x4 a1 = *(const u32x4*)(kt + k_off + (((2 * ks + 2 + kg) ^ k_swz) * 16));
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), __builtin_bit_cast(bf16x8, qf[ks]), s, 0, 0, 0);
-      s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), __builtin_bit_cast(bf16x8, qf[ks + 1]), s2, 0, 0, 0);
+      for (int r = 0; r < 16; ++r) s2[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ks += 2) {
+        const u32x4 a0 = *(const u32x4*)(kt + k_off + (((2 * ks + kg) ^ k_swz) * 16));
+        const u32x4 a1 = *(const u32x4*)(kt + k_off + (((2 * ks + 2 + kg) ^ k_swz) * 16));
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), __builtin_bit_cast(bf16x8, qf[ks]), s, 0, 0, 0);
+        s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), __builtin_bit_cast(bf16x8, qf[ks + 1]), s2, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] += s2[r];
     }
     const int kb = t * KT + 32 * sb;
     float mx = NEG;
@@ -179,25 +214,27 @@ __global__ __launch_bounds__(128 * CW) void attn_tree_bf16_kernel(AttnParams p) 
       vis >>= 4 * kg;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float v = ((vis >> (8 * (r >> 2) + (r & 3))) & 1u) ? (s[r] + s2[r]) * p.scale_log2 : NEG;
+        const float v = ((vis >> (8 * (r >> 2) + (r & 3))) & 1u) ? s[r] : NEG;
         s[r] = v;
         mx = fmaxf(mx, v);
       }
     } else {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        s[r] = (s[r] + s2[r]) * p.scale_log2;
-        mx = fmaxf(mx, s[r]);
-      }
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[r]);
     }
+    mx *= p.scale_log2;                                 // the scale is positive: max and scaling commute
     float xa, xb;
     pair_values(mx, xa, xb);
-    const float m_new = fmaxf(m_run, fmaxf(xa, xb));
+    const float m_cand = fmaxf(m_run, fmaxf(xa, xb));
+    // The running max only moves when some row of the wavefront would raise its own by more than MAX_SLACK
+    // (log2 units): until then exp2 may exceed 1 by up to 2^MAX_SLACK, which the fp32 sums and the head/tail
+    // split carry without loss, and the 64 output registers need no rescaling in most tiles.
+    const float m_new = __any(m_cand - m_run > MAX_SLACK) ? m_cand : m_run;
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     float ls = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      s[r] = __builtin_amdgcn_exp2f(s[r] - m_new);
+      s[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], p.scale_log2, -m_new));
       ls += s[r];
     }
     pair_values(ls, xa, xb);
@@ -209,20 +246,28 @@ __global__ __launch_bounds__(128 * CW) void attn_tree_bf16_kernel(AttnParams p) 
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
     }
-    // O^T += V^T P^T.  Operand m of P^T holds keys 32 sb + 16 m + {4kg..4kg+3, 8+4kg..8+4kg+3} = registers 8m..8m+7.
+    // Operand m of P^T holds keys 32 sb + 16 m + {4kg..4kg+3, 8+4kg..8+4kg+3} = registers 8m..8m+7.
     // exp(S) is split into a bf16 head and a bf16 tail (p = hi + lo, 16 significant bits) and both are
     // multiplied with V: rounding P to a single bf16 would put a 2^-9 relative error on the attention output,
     // which the following RMSNorm can magnify when the residual stream is small.
 #pragma unroll
-    for (int m = 0; m < 2; ++m) {
-      u32x4 ph, pl;
+    for (int m = 0; m < 2; ++m)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const float p0 = s[8 * m + 2 * j], p1 = s[8 * m + 2 * j + 1];
         const uint32_t h = pack_bf16x2(p0, p1);
-        ph[j] = h;
-        pl[j] = pack_bf16x2(p0 - __uint_as_float(h << 16), p1 - __uint_as_float(h & 0xFFFF0000u));
+        ph[m][j] = h;
+        // tail = p - head, one v_dot2c_f32_bf16 each: p + head.lo * -1 + head.hi * 0 (exact)
+        const float t0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, h), __builtin_bit_cast(bf16x2_t, minus_lo), p0, false);
+        const float t1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, h), __builtin_bit_cast(bf16x2_t, minus_hi), p1, false);
+        pl[m][j] = pack_bf16x2(t0, t1);
       }
+  };
+  // O^T += V^T P^T for tile t
+  auto value_tile = [&](int t, const u32x4 (&ph)[2], const u32x4 (&pl)[2]) {
+    const unsigned char* vt = smem + ((t - t_begin) % RD) * TILE_BYTES + KT * ROWB;
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
 #pragma unroll
       for (int db = 0; db < 4; ++db) {
         short4v lo4, hi4;
@@ -233,19 +278,17 @@ __global__ __launch_bounds__(128 * CW) void attn_tree_bf16_kernel(AttnParams p) 
         }
         typedef short short8v __attribute__((ext_vector_type(8)));
         const short8v a = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, ph),
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, ph[m]),
                                                        o[db], 0, 0, 0);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, pl),
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, pl[m]),
                                                        o[db], 0, 0, 0);
       }
     }
   };
 
-  // Ring of RD tiles: tiles t_begin .. t_begin + RD - 2 first, then per iteration the tile RD - 1 ahead, into the
-  // slot that the barrier has just freed.  Loads complete in issue order, so "at most (RD - 2) tiles' worth of my
-  // loads in flight" means that my part of tile t has landed; the barrier extends that to every wavefront's part.
-#pragma unroll
-  for (int i = 0; i < RD - 1; ++i) issue_tile(t_begin + i);
+  // Two tile slots: tile t + 1 is requested when the barrier of iteration t has freed its slot and arrives while
+  // tile t is worked on.  (Deeper rings were slower: the first tile waits behind everything requested before it.)
+  if (t_begin < t_end) issue_tile(t_begin);
   // The query fragments and mask words are ordinary loads issued AFTER those tiles, so that both latencies run
   // side by side; the compiler's wait for them (at their first use, just below) also covers every direct load
   // issued so far, and the counted waits in the loop only ever see direct loads younger than that.
@@ -261,11 +304,15 @@ __global__ __launch_bounds__(128 * CW) void attn_tree_bf16_kernel(AttnParams p) 
   for (int ks = 0; ks < 8; ++ks) asm volatile("" ::"v"(qf[ks]));
 #pragma unroll
   for (int w = 0; w < 4; ++w) asm volatile("" ::"v"(mw[w]));
+  u32x4 ph[2], pl[2];
   for (int t = t_begin; t < t_end; ++t) {
-    ATTN_WAIT_LOADS((RD - 2) * 2 * IPW);
+    ATTN_WAIT_LOADS(0);                        // my part of tile t has landed; the barrier extends that to everyone's
     __syncthreads();
-    issue_tile(t + RD - 1);
-    if (wave_active) compute_tile(t);
+    if (t + 1 < t_end) issue_tile(t + 1);
+    if (wave_active) {
+      score_tile(t, ph, pl);
+      value_tile(t, ph, pl);
+    }
   }
   ATTN_WAIT_LOADS(0);                          // nothing may still be writing LDS when it is reused or released
 
@@ -415,8 +462,8 @@ size_t attention_scratch_floats(int R, int H, int d, int max_splits) {
 
 template <int CW>
 static hipError_t launch_attn_cw(const AttnParams& p, int grid, hipStream_t st) {
-  constexpr int LDS = attn_ring(CW) * TILE_BYTES;
-  static_assert(LDS >= CW * 66 * 64 * 4, "the end-of-kernel merge reuses the tile ring");
+  // the tile ring, reused by the end-of-kernel merge of the two key-block halves
+  constexpr int LDS = RD * TILE_BYTES > CW * 66 * 64 * 4 ? RD * TILE_BYTES : CW * 66 * 64 * 4;
   auto kernel = attn_tree_bf16_kernel<CW>;
   static bool configured = false;                // per process; the attribute belongs to the code object
   if (!configured) {

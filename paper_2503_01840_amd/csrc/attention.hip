@@ -80,7 +80,7 @@ constexpr int RD = 2;                        // tiles in LDS: the one being work
 // softmax, 16 value MFMAs) is what bounds a wavefront, so it is cut in two and the halves are merged through
 // LDS at the end.
 template <int CW>
-__global__ __launch_bounds__(128 * CW) void attn_tree_bf16_kernel(AttnParams p) {
+__global__ __launch_bounds__(128 * CW, CW == 1 ? 1 : 2) void attn_tree_bf16_kernel(AttnParams p) {
   constexpr int NW = 2 * CW;
   constexpr int IPW = 16 / NW;                 // direct loads per wavefront per tile, for K and again for V
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];

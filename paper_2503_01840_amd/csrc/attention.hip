@@ -437,14 +437,24 @@ __global__ __launch_bounds__(256) void attn_tree_f32_kernel(const float* __restr
 
 }  // namespace
 
-static int attn_cw(int rows_per_group) { return rows_per_group <= 32 ? 1 : rows_per_group <= 64 ? 2 : 4; }
+// Wavefront pairs per workgroup.  More than 64 rows per KV head can go to 8-wavefront workgroups (two wavefronts
+// on every SIMD, which overlap each other's MFMA and softmax phases: ~0.8 us of SIMD time per wavefront-tile
+// against 1.3 us for a lone wavefront) or to 4-wavefront ones (half as many key splits for the same number of
+// workgroups, so half the partial results to write and merge).  The first pays once every SIMD has more than
+// about a dozen wavefront-tiles to work through (measured crossover at 240 rows: between 4096 and 8192 keys).
+static int attn_cw(int B, int rows_per_group, int Hkv, int max_len) {
+  if (rows_per_group <= 32) return 1;
+  if (rows_per_group <= 64) return 2;
+  const long wave_tiles = (long)B * Hkv * ((rows_per_group + 31) / 32) * 2 * ((max_len + KT - 1) / KT);
+  return wave_tiles <= 12 * 1024 ? 2 : 4;
+}
 
 int attention_pick_splits(int B, int rows_per_seq, int H, int Hkv, int max_len) {
-  const int G = H / Hkv, cw = attn_cw(G * rows_per_seq);
+  const int G = H / Hkv, cw = attn_cw(B, G * rows_per_seq, Hkv, max_len);
   const int qblocks = (G * rows_per_seq + 32 * cw - 1) / (32 * cw);
   const int base = B * Hkv * qblocks;
   const int tiles = (max_len + KT - 1) / KT;
-  const int slots = cw == 4 ? 256 : 512;         // workgroups resident at once
+  const int slots = cw == 1 ? 512 : 256;         // one workgroup per CU, two of the smallest kind
   int s = (slots + base - 1) / base;
   s = s < 1 ? 1 : s;
   // a batch that already fills the chip is still cut in two: its sequences differ in length, workgroups are
@@ -487,7 +497,7 @@ hipError_t launch_tree_attention(bool bf16, const void* q, const void* kcache, c
     return hipGetLastError();
   }
   if (d != D || H % Hkv) return hipErrorInvalidValue;
-  const int cw = attn_cw(H / Hkv * rows_per_seq);
+  const int cw = attn_cw(B, H / Hkv * rows_per_seq, Hkv, max_len);
   AttnParams p;
   p.q = (const bf16_t*)q; p.kc = (const bf16_t*)kcache; p.vc = (const bf16_t*)vcache;
   p.seq = seq; p.mask = mask;

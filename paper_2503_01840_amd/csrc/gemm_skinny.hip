@@ -212,6 +212,165 @@ __global__ __launch_bounds__(256, GEMM_OCC) void gemm_skinny_kernel(GemmParams p
   }
 }
 
+// ---- 128 weight rows per workgroup, for 33..64 activation rows ----
+//
+// Every 16-byte load a wavefront issues, weight or activation, takes one of the CU's ~200 in-order slots for
+// outstanding vector-memory lines, and an activation line that only comes from L2 holds its slot as long as
+// the HBM lines queued before it.  With 64 weight rows per workgroup a 64-row activation tile is as many lines
+// per stage as the weights (hardware counters: ~95 HBM lines in flight per CU, against ~135 for the 32-row
+// kernel and ~185 for a pure weight stream); with 128 weight rows it is half as many.  Eight wavefronts = 2
+// halves of the weight rows x 4 quarters of the stage's K; the activation stage (16 KiB, contiguous in the
+// fragment-major layout) goes through LDS once instead of being fetched by each half.
+namespace wide_tile {
+constexpr int BN2 = 128;
+constexpr int W_BYTES = BN2 * WROW;                  // one staged weight tile
+constexpr int X_BYTES = 64 * BK * 2;                 // one staged activation tile (two 32-row halves x BK/16 k-steps)
+constexpr int STAGE_BYTES = W_BYTES + X_BYTES;
+constexpr int RED_BYTES = 8 * 64 * RED_LD * 4;
+constexpr int SMEM2 = 2 * STAGE_BYTES > RED_BYTES ? 2 * STAGE_BYTES : RED_BYTES;
+constexpr int XCH = X_BYTES / 16 / 512;              // 16-byte activation chunks per thread per stage
+}  // namespace wide_tile
+
+__device__ __forceinline__ const bf16_t* weight_row128(const GemmParams& p, int tile, int row) {
+  if (p.mode == 1) {                                   // 64 gate rows | 64 up rows
+    int r = tile * 64 + (row & 63);
+    r = min(r, p.rows[0] - 1);
+    return p.w[row >> 6] + (size_t)r * p.K;
+  }
+  int n = min(tile * wide_tile::BN2 + row, p.N - 1);
+  int m = 0;
+  while (m + 1 < p.nmat && n >= p.rows[m]) { n -= p.rows[m]; ++m; }
+  return p.w[m] + (size_t)n * p.K;
+}
+
+__global__ __launch_bounds__(512) void gemm_skinny128_kernel(GemmParams p) {
+  using namespace wide_tile;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem2[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int rh = wave >> 2, kq = wave & 3;
+  const int tile = blockIdx.x, split = blockIdx.y, mtile = blockIdx.z;
+  const int Kc = p.K / p.S, k_begin = split * Kc, KT = Kc / BK;
+
+  const bf16_t* wptr[WCH];
+  int wlds[WCH];
+#pragma unroll
+  for (int i = 0; i < WCH; ++i) {
+    const int c = tid + 512 * i, row = c / CPR, col = c % CPR;
+    wptr[i] = weight_row128(p, tile, row) + k_begin + col * 8;
+    wlds[i] = row * WROW + col * 16;
+  }
+  // the activation stage kt: BK/16 k-steps x 2 halves x 1 KiB, contiguous
+  const bf16_t* xptr = p.x + ((size_t)mtile * (p.K >> 4) + (k_begin >> 4)) * 2 * 512 + (size_t)tid * 8;
+
+  u32x4 wreg[PF][WCH];
+  u32x4 xreg[PF][XCH];
+  const int rot = (tile * GEMM_ROT_MUL + split) % KT;
+  auto load_stage = [&](int kt0_, int slot) {
+    int kt = kt0_ + rot;
+    kt = kt >= KT ? kt - KT : kt;
+#pragma unroll
+    for (int i = 0; i < WCH; ++i) wreg[slot][i] = *(const u32x4*)(wptr[i] + (size_t)kt * BK);
+#pragma unroll
+    for (int i = 0; i < XCH; ++i) xreg[slot][i] = *(const u32x4*)(xptr + (size_t)kt * (X_BYTES / 2) + i * 512 * 8);
+  };
+  floatx16 acc[2][2];                                  // [activation half][32 weight rows]
+#pragma unroll
+  for (int mh = 0; mh < 2; ++mh)
+#pragma unroll
+    for (int nh = 0; nh < 2; ++nh)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mh][nh][r] = 0.f;
+
+  const int b_off = (rh * 64 + (lane & 31)) * WROW + (kq * (BK / 4) + 8 * (lane >> 5)) * 2;
+  const int a_off = W_BYTES + kq * KSW * 2048 + lane * 16;
+  auto do_stage = [&](int kt, int s, bool refill) {
+    unsigned char* buf = smem2 + (kt & 1) * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < WCH; ++i) *(u32x4*)(buf + wlds[i]) = wreg[s][i];
+#pragma unroll
+    for (int i = 0; i < XCH; ++i) *(u32x4*)(buf + W_BYTES + (tid + 512 * i) * 16) = xreg[s][i];
+    if (refill) load_stage(kt + PF, s);
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < KSW; ++ks) {
+      u32x4 a[2];
+#pragma unroll
+      for (int mh = 0; mh < 2; ++mh) a[mh] = *(const u32x4*)(buf + a_off + (ks * 2 + mh) * 1024);
+#pragma unroll
+      for (int nh = 0; nh < 2; ++nh) {
+        const u32x4 b = *(const u32x4*)(buf + nh * 32 * WROW + b_off + ks * 32);
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh)
+          acc[mh][nh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              __builtin_bit_cast(bf16x8, a[mh]), __builtin_bit_cast(bf16x8, b), acc[mh][nh], 0, 0, 0);
+      }
+    }
+  };
+  auto drain = [&](int kt0) {
+    for (; kt0 < KT; kt0 += PF) {
+#pragma unroll
+      for (int s = 0; s < PF; ++s) {
+        const int kt = kt0 + s;
+        if (kt < KT) do_stage(kt, s, kt + PF < KT);
+      }
+    }
+  };
+  if (KT >= 2 * PF) {
+#pragma unroll
+    for (int s = 0; s < PF; ++s) {
+      load_stage(s, s);
+      __builtin_amdgcn_sched_barrier(0);      // keep the issue order: the loop's wait counts depend on it
+    }
+    int kt0 = 0;
+    for (; kt0 + 2 * PF <= KT; kt0 += PF) {
+#pragma unroll
+      for (int s = 0; s < PF; ++s) do_stage(kt0 + s, s, true);
+    }
+    drain(kt0);
+  } else {
+#pragma unroll
+    for (int s = 0; s < PF; ++s)
+      if (s < KT) load_stage(s, s);
+    drain(0);
+  }
+
+  // sum the four K-quarter tiles of each weight-row half through LDS: red[wave][activation row][weight row]
+  __syncthreads();
+  float* red = (float*)smem2;
+#pragma unroll
+  for (int mh = 0; mh < 2; ++mh)
+#pragma unroll
+    for (int nh = 0; nh < 2; ++nh)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int tok = mh * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        red[(wave * 64 + tok) * RED_LD + nh * 32 + (lane & 31)] = acc[mh][nh][r];
+      }
+  __syncthreads();
+  auto summed = [&](int half, int tok, int f) {
+    const float* r0 = red + ((half * 4) * 64 + tok) * RED_LD + f;
+    return r0[0] + r0[64 * RED_LD] + r0[128 * RED_LD] + r0[192 * RED_LD];
+  };
+  if (p.epi == GEMM_EPI_PARTIAL) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int idx = tid + 512 * e, tok = idx >> 7, f = idx & 127;
+      const float v = summed(f >> 6, tok, f & 63);
+      const int row = mtile * 64 + tok, n = tile * BN2 + f;
+      if (row < p.M && n < p.N) p.out_f32[((size_t)split * p.M + row) * p.N + n] = v;
+    }
+  } else {
+    const int I = p.N >> 1;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int idx = tid + 512 * e, tok = idx >> 6, f = idx & 63;
+      const float g = summed(0, tok, f), u = summed(1, tok, f);
+      const int row = mtile * 64 + tok, n = tile * 64 + f;
+      if (row < p.M && n < I) p.out_xf[xf_offset(row, n, I)] = f32_to_bf16(g / (1.f + expf(-g)) * u);
+    }
+  }
+}
+
 }  // namespace
 
 // Split-K factor: the smallest divisor of the stage count that puts at least ~3/4 of a workgroup per CU
@@ -240,6 +399,22 @@ hipError_t launch_gemm_skinny(const bf16_t* x, const GemmWeights& W, int M, int 
   p.nmat = W.nmat; p.mode = W.mode;
   p.M = M; p.N = N; p.K = K; p.S = S; p.epi = epi;
   p.out_f32 = (float*)out; p.out_xf = (bf16_t*)out;
+  // 33..64 rows: 128 weight rows per workgroup where that still gives most CUs a tile without split-K (gate/up,
+  // LM head: 5 % faster); matrices with few rows need the splits for parallelism and then the smaller
+  // workgroup's shorter prologue and reduction win (q/k/v, o, down: 5-15 % slower with the large tile)
+  const int tiles128 = W.mode == 1 ? (N / 2 + 63) / 64 : (N + wide_tile::BN2 - 1) / wide_tile::BN2;
+  if (M > 32 && S == 1 && tiles128 >= 192) {
+    const int tiles = tiles128;
+    static bool configured = false;              // per process; the attribute belongs to the code object
+    if (!configured) {
+      hipError_t e = hipFuncSetAttribute((const void*)gemm_skinny128_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         wide_tile::SMEM2);
+      if (e != hipSuccess) return e;
+      configured = true;
+    }
+    hipLaunchKernelGGL(gemm_skinny128_kernel, dim3(tiles, S, (M + 63) / 64), dim3(512), wide_tile::SMEM2, st, p);
+    return hipGetLastError();
+  }
   const int tiles = W.mode == 1 ? (N / 2 + 31) / 32 : (N + BN - 1) / BN;
   dim3 grid(tiles, S, (M + 63) / 64);
   if (M <= 32)

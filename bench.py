@@ -135,7 +135,7 @@ def main():
                     "peak": None, "unit": "GB/s", "frac": None, "traffic": None,
                     "step_algorithmic_GB": ab["step"] / 1e9, "step_GBps": ab["step"] / ms_per_step / 1e6}
     else: roofline = {
-        "bound": "hbm", "kernel": "gemm_skinny_kernel<2> (verification GEMMs, 60 activation rows)",
+        "bound": "hbm", "kernel": "gemm_skinny_kernel<2> + gemm_skinny128_kernel (the verification GEMMs, 60 activation rows)",
         "achieved": g_bytes / g_ms / 1e6, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": g_bytes / g_ms / 1e6 / HBM_PEAK_GBPS, "traffic": stored_traffic(args.config),
         "launches_per_step": g_n, "avg_launch_us": g_ms / g_n * 1e3, "bytes_per_launch": g_bytes / g_n,

@@ -129,6 +129,16 @@ def test_verify_more_than_64_rows_uses_the_wide_gemm_path():
             assert np.max(np.abs(taps[:, b].cpu().numpy() - ref["taps"])) < 2e-2, (B, N, b)
 
 
+def test_verify_33_to_64_rows_on_large_ragged_matrices():
+    """33, 48 and 64 tree nodes against an LM head of 24613 rows (192 tiles of 128 weight rows and a ragged one) and a
+    12416-wide gate/up pair: the launches that take the 128-weight-row workgroups, with a K of only two stages."""
+    shape = SMALL.with_(name="small-wide", n_layers=1, taps=(0, 0, 0), intermediate=12416, vocab=24613)
+    model = PL.OracleModel(shape)
+    ctx = _ctx(shape)
+    for i, N in enumerate((33, 48, 64)):
+        _verify_case(ctx, shape, model, S.random_tree(S.SEED, 40 + i, N, 6, 8)[0], 70 + i, seed_salt=20 + i)
+
+
 @pytest.mark.parametrize("n_new,D,K,N", [(8, 3, 3, 10), (1, 4, 1, 5), (2, 1, 4, 5), (1, 2, 16, 40), (3, 8, 2, 30)])
 def test_draft_expand_shapes(n_new, D, K, N):
     E = _E()

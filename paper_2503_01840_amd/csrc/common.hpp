@@ -2,6 +2,7 @@
 // layout read by the MFMA GEMMs, and small reductions.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -118,4 +119,13 @@ __device__ __forceinline__ float block_max(float v, float* red) {
   }
   __syncthreads();
   return red[16];
+}
+
+// Launch with an optional start/stop event pair attached to the dispatch itself: the events then carry the
+// kernel's own begin and end timestamps (what a kernel trace reports), not the time between two stream markers.
+template <typename Kernel, typename Params>
+inline void launch_with_events(Kernel kernel, dim3 grid, dim3 block, unsigned lds_bytes, hipStream_t st, hipEvent_t ev_start,
+                               hipEvent_t ev_stop, const Params& p) {
+  if (ev_start && ev_stop) hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, st, ev_start, ev_stop, 0, p);
+  else hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, p);
 }

@@ -112,11 +112,11 @@ struct eagle3_ctx {
               float* direct_out = nullptr) {
     if (bf16 && M > 64) {
       Stamp* sp = profiling && stamps_used < stamps.size() ? &stamps[stamps_used++] : nullptr;
-      if (sp) { sp->bytes = 2.0 * N * K; sp->wide = true; CK(hipEventRecord(sp->a, st)); }
+      if (sp) { sp->bytes = 2.0 * N * K; sp->wide = true; }
       int S = 1;
       void* out = epi == GEMM_EPI_SWIGLU ? act_h : (direct_out ? (void*)direct_out : (void*)part);
-      CK(launch_gemm_wide((const bf16_t*)act_in, W, M, N, K, epi, out, direct_out ? 0 : part_floats, &S, st));
-      if (sp) CK(hipEventRecord(sp->b, st));
+      CK(launch_gemm_wide((const bf16_t*)act_in, W, M, N, K, epi, out, direct_out ? 0 : part_floats, &S, st,
+                          sp ? sp->a : nullptr, sp ? sp->b : nullptr));
       if (S_out) *S_out = S;
       return EAGLE3_OK;
     }
@@ -126,9 +126,8 @@ struct eagle3_ctx {
       if (epi == GEMM_EPI_PARTIAL && direct_out == nullptr && (size_t)S * M * N > part_floats) return EAGLE3_E_STATE;
       void* out = epi == GEMM_EPI_SWIGLU ? act_h : (direct_out && S == 1 ? (void*)direct_out : (void*)part);
       Stamp* sp = profiling && stamps_used < stamps.size() ? &stamps[stamps_used++] : nullptr;
-      if (sp) { sp->bytes = 2.0 * N * K; sp->wide = M > 32; CK(hipEventRecord(sp->a, st)); }
-      CK(launch_gemm_skinny((const bf16_t*)act_in, W, M, N, K, S, epi, out, st));
-      if (sp) CK(hipEventRecord(sp->b, st));
+      if (sp) { sp->bytes = 2.0 * N * K; sp->wide = M > 32; }
+      CK(launch_gemm_skinny((const bf16_t*)act_in, W, M, N, K, S, epi, out, st, sp ? sp->a : nullptr, sp ? sp->b : nullptr));
       if (direct_out && S > 1) CK(launch_reduce_partials(part, S, M, N, direct_out, st));
       if (S_out) *S_out = S;
       return EAGLE3_OK;

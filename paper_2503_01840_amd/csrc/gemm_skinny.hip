@@ -390,7 +390,7 @@ int gemm_skinny_pick_splits(int N, int K, int M) {
 }
 
 hipError_t launch_gemm_skinny(const bf16_t* x, const GemmWeights& W, int M, int N, int K, int S, int epi, void* out,
-                              hipStream_t st) {
+                              hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (M <= 0 || N <= 0 || K <= 0 || S <= 0 || K % (BK * S) != 0) return hipErrorInvalidValue;
   if (epi == GEMM_EPI_SWIGLU && (S != 1 || W.mode != 1)) return hipErrorInvalidValue;
   GemmParams p;
@@ -412,14 +412,14 @@ hipError_t launch_gemm_skinny(const bf16_t* x, const GemmWeights& W, int M, int 
       if (e != hipSuccess) return e;
       configured = true;
     }
-    hipLaunchKernelGGL(gemm_skinny128_kernel, dim3(tiles, S, (M + 63) / 64), dim3(512), wide_tile::SMEM2, st, p);
+    launch_with_events(gemm_skinny128_kernel, dim3(tiles, S, (M + 63) / 64), dim3(512), wide_tile::SMEM2, st, ev_start, ev_stop, p);
     return hipGetLastError();
   }
   const int tiles = W.mode == 1 ? (N / 2 + 31) / 32 : (N + BN - 1) / BN;
   dim3 grid(tiles, S, (M + 63) / 64);
   if (M <= 32)
-    hipLaunchKernelGGL(gemm_skinny_kernel<1>, grid, dim3(256), 0, st, p);
+    launch_with_events(gemm_skinny_kernel<1>, grid, dim3(256), 0, st, ev_start, ev_stop, p);
   else
-    hipLaunchKernelGGL(gemm_skinny_kernel<2>, grid, dim3(256), 0, st, p);
+    launch_with_events(gemm_skinny_kernel<2>, grid, dim3(256), 0, st, ev_start, ev_stop, p);
   return hipGetLastError();
 }

@@ -231,7 +231,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, OCC) void gemm_wide_kernel(WidePara
 }
 
 template <int WGM, int WGN, int FM, int FN, int OCC>
-hipError_t launch_cfg(WideParams& p, int S, hipStream_t st) {
+hipError_t launch_cfg(WideParams& p, int S, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   constexpr int TM = 32 * FM * WGM, TN = 32 * FN * WGN;
   constexpr int LDS = A_SLOTS * TM * (BK / 2) * 2 + B_SLOTS * TN * BK * 2;
   auto kernel = gemm_wide_kernel<WGM, WGN, FM, FN, OCC>;
@@ -244,7 +244,7 @@ hipError_t launch_cfg(WideParams& p, int S, hipStream_t st) {
   p.tiles = (p.N + TN - 1) / TN;
   p.groups = (p.tiles + 7) / 8;
   p.mblocks = (p.M + TM - 1) / TM;
-  hipLaunchKernelGGL(kernel, dim3(8 * p.groups * p.mblocks * S), dim3(64 * WGM * WGN), LDS, st, p);
+  launch_with_events(kernel, dim3(8 * p.groups * p.mblocks * S), dim3(64 * WGM * WGN), LDS, st, ev_start, ev_stop, p);
   return hipGetLastError();
 }
 
@@ -254,7 +254,7 @@ int g_gemm_wide_force_cfg = -1, g_gemm_wide_force_S = -1;   // tuning hooks (ben
 
 // Picks the tile shape and the split-K factor, then launches.
 hipError_t launch_gemm_wide(const bf16_t* x, const GemmWeights& W, int M, int N, int K, int epi, void* out,
-                            size_t out_capacity_floats, int* S_out, hipStream_t st) {
+                            size_t out_capacity_floats, int* S_out, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (M <= 0 || N <= 0 || K <= 0 || K % BK || N % 4) return hipErrorInvalidValue;
   if (epi == GEMM_EPI_SWIGLU ? (W.mode != 1 || N % 8) : W.mode != 0) return hipErrorInvalidValue;
   WideParams p;
@@ -292,5 +292,5 @@ hipError_t launch_gemm_wide(const bf16_t* x, const GemmWeights& W, int M, int N,
     S = g_gemm_wide_force_S;
   p.S = S;
   if (S_out) *S_out = S;
-  return cfg == 0 ? launch_cfg<2, 4, 4, 2, 1>(p, S, st) : launch_cfg<2, 2, 2, 2, 2>(p, S, st);
+  return cfg == 0 ? launch_cfg<2, 4, 4, 2, 1>(p, S, st, ev_start, ev_stop) : launch_cfg<2, 2, 2, 2, 2>(p, S, st, ev_start, ev_stop);
 }

@@ -22,16 +22,17 @@ enum { GEMM_EPI_PARTIAL = 0, GEMM_EPI_SWIGLU = 1 };
 //   x      fragment-major bf16 [ceil64(M), K] (see xf_offset)
 //   out    epi PARTIAL: fp32 [S, M, N] (split-K partial sums, S = splits); the consumer adds them
 //          epi SWIGLU : fragment-major bf16 [ceil64(M), N/2] = silu(gate) * up   (requires S == 1)
-// Requires K % (128*S) == 0.  N = total weight rows.
+// Requires K % (128*S) == 0.  N = total weight rows.  ev_start / ev_stop (optional): events attached to the dispatch.
 hipError_t launch_gemm_skinny(const bf16_t* x, const GemmWeights& W, int M, int N, int K, int S, int epi,
-                              void* out, hipStream_t st);
+                              void* out, hipStream_t st, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 // Chooses the split-K factor for a [N, K] weight so that about two workgroups per CU are resident.
 int gemm_skinny_pick_splits(int N, int K, int M);
 
 // The same product for many rows (M > 64): MFMA-bound tiling, see gemm_wide.hip.  Chooses tile shape and split-K
 // itself (S <= what fits into out_capacity_floats; 0 forces S = 1) and reports S.
 hipError_t launch_gemm_wide(const bf16_t* x, const GemmWeights& W, int M, int N, int K, int epi, void* out,
-                            size_t out_capacity_floats, int* S_out, hipStream_t st);
+                            size_t out_capacity_floats, int* S_out, hipStream_t st, hipEvent_t ev_start = nullptr,
+                            hipEvent_t ev_stop = nullptr);
 
 // fp32 reference-quality GEMM: out[m, col0 + n] = sum_k x[m,k] w[n,k]; x [M,K], w [N,K], out row stride ld.
 hipError_t launch_gemm_f32(const float* x, const float* w, int M, int N, int K, float* out, int ld, int col0,

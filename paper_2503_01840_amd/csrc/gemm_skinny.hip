@@ -1,7 +1,8 @@
 // Weight-streaming bf16 GEMM for few activation rows:  Y[M, N] = X[M, K] * W[N, K]^T, fp32 accumulate.
 //
 // Every projection of the speculative step (fusion FC, q/k/v, o, gate/up, down, both LM heads) has at
-// most a few dozen rows per sequence, so the kernel is bound by reading W once from HBM.  Design:
+// most a few dozen rows per sequence, so the kernel is bound by reading W once from HBM.  Two kernels: the
+// one described here, and further down a variant with 128 weight rows per workgroup for the largest matrices.
 //   * one workgroup (4 wavefronts) owns 64 weight rows and one K range (split-K over blockIdx.y);
 //   * W is read with 16-byte loads that are contiguous per row (16 lanes = 256 B of one row), staged
 //     through registers into a double-buffered, row-padded LDS tile, and read back as MFMA B operands;
@@ -15,25 +16,14 @@
 
 namespace {
 
-#ifndef GEMM_BK
-#define GEMM_BK 128
-#endif
-constexpr int BK = GEMM_BK;             // k per stage (128 or 256)
+constexpr int BK = 128;                 // k per stage: 256-byte pieces of a weight row
 constexpr int WCH = BK / 32;            // 16-byte weight chunks per thread per stage
 constexpr int KSW = BK / 64;            // MFMA k-steps per wavefront per stage
 constexpr int CPR = BK / 8;             // 16-byte chunks per weight row per stage
 constexpr int BN = 64;                  // weight rows per workgroup
 constexpr int WROW = BK * 2 + 16;       // LDS bytes per staged weight row (padded)
-#ifndef GEMM_PF
-#define GEMM_PF 4
-#endif
-#ifndef GEMM_OCC
-#define GEMM_OCC 2
-#endif
-#ifndef GEMM_ROT_MUL
-#define GEMM_ROT_MUL 5
-#endif
-constexpr int PF = GEMM_PF;             // stages in flight
+constexpr int PF = 4;                   // stages in flight (5 and more spill the prefetch ring to scratch)
+constexpr int ROT_MUL = 5;              // stagger of the starting stage from tile to tile
 constexpr int RED_LD = 65;              // floats per row of the reduction buffer
 constexpr int SMEM_BYTES = 4 * 64 * RED_LD * 4 > 2 * BN * WROW ? 4 * 64 * RED_LD * 4 : 2 * BN * WROW;
 
@@ -62,7 +52,7 @@ __device__ __forceinline__ const bf16_t* weight_row(const GemmParams& p, int til
 }
 
 template <int MH>
-__global__ __launch_bounds__(256, GEMM_OCC) void gemm_skinny_kernel(GemmParams p) {
+__global__ __launch_bounds__(256, 2) void gemm_skinny_kernel(GemmParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tile = blockIdx.x, split = blockIdx.y, mtile = blockIdx.z;
@@ -81,33 +71,21 @@ __global__ __launch_bounds__(256, GEMM_OCC) void gemm_skinny_kernel(GemmParams p
 
   u32x4 wreg[PF][WCH];
   u32x4 xreg[PF][KSW][MH];
-#ifdef GEMM_NOROT
-  const int rot = 0;
-#else
   // Workgroups walk their K range from staggered starting stages: with power-of-two row strides, all
   // workgroups reading the same k offset at the same time would hammer the same few HBM channels.
-  const int rot = (tile * GEMM_ROT_MUL + split) % KT;
-#endif
+  const int rot = (tile * ROT_MUL + split) % KT;
   auto load_stage = [&](int kt0_, int slot) {
     int kt = kt0_ + rot;
     kt = kt >= KT ? kt - KT : kt;
 #pragma unroll
     for (int i = 0; i < WCH; ++i) {
-#ifdef GEMM_NT
-      wreg[slot][i] = __builtin_nontemporal_load((const u32x4*)(wptr[i] + (size_t)kt * BK));
-#else
       wreg[slot][i] = *(const u32x4*)(wptr[i] + (size_t)kt * BK);
-#endif
     }
 #pragma unroll
     for (int ks = 0; ks < KSW; ++ks)
 #pragma unroll
       for (int mh = 0; mh < MH; ++mh)
-#ifdef GEMM_NOX
-        xreg[slot][ks][mh] = (u32x4){(uint32_t)kt, 1u, 2u, 3u};
-#else
         xreg[slot][ks][mh] = *(const u32x4*)(xptr + ((size_t)(kt * (BK / 16) + ks) * 2 + mh) * 512);
-#endif
   };
   floatx16 acc[MH][2];
 #pragma unroll
@@ -264,7 +242,7 @@ __global__ __launch_bounds__(512) void gemm_skinny128_kernel(GemmParams p) {
 
   u32x4 wreg[PF][WCH];
   u32x4 xreg[PF][XCH];
-  const int rot = (tile * GEMM_ROT_MUL + split) % KT;
+  const int rot = (tile * ROT_MUL + split) % KT;
   auto load_stage = [&](int kt0_, int slot) {
     int kt = kt0_ + rot;
     kt = kt >= KT ? kt - KT : kt;

@@ -250,8 +250,6 @@ hipError_t launch_cfg(WideParams& p, int S, hipStream_t st, hipEvent_t ev_start,
 
 }  // namespace
 
-int g_gemm_wide_force_cfg = -1, g_gemm_wide_force_S = -1;   // tuning hooks (benchmarks only)
-
 // Picks the tile shape and the split-K factor, then launches.
 hipError_t launch_gemm_wide(const bf16_t* x, const GemmWeights& W, int M, int N, int K, int epi, void* out,
                             size_t out_capacity_floats, int* S_out, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
@@ -283,13 +281,6 @@ hipError_t launch_gemm_wide(const bf16_t* x, const GemmWeights& W, int M, int N,
     cfg = 1;
     pick(128, 128, 384, 8, &S);
   }
-  if (g_gemm_wide_force_cfg >= 0) {
-    cfg = g_gemm_wide_force_cfg;
-    if (cfg == 0) pick(256, 256, 160, 16, &S); else pick(128, 128, 384, 8, &S);
-  }
-  if (epi == GEMM_EPI_PARTIAL && g_gemm_wide_force_S > 0 && KT % g_gemm_wide_force_S == 0 &&
-      (size_t)g_gemm_wide_force_S * M * N <= out_capacity_floats)
-    S = g_gemm_wide_force_S;
   p.S = S;
   if (S_out) *S_out = S;
   return cfg == 0 ? launch_cfg<2, 4, 4, 2, 1>(p, S, st, ev_start, ev_stop) : launch_cfg<2, 2, 2, 2, 2>(p, S, st, ev_start, ev_stop);

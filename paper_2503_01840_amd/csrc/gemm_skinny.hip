@@ -351,9 +351,13 @@ __global__ __launch_bounds__(512) void gemm_skinny128_kernel(GemmParams p) {
 
 }  // namespace
 
-// Split-K factor: the smallest divisor of the stage count that puts at least ~3/4 of a workgroup per CU
-// in flight (measured on MI355X: 192-256 workgroups already stream a [4096..6144, 4096] weight at its best
-// rate, and every extra split adds an fp32 partial tile the consumer has to read back).
+// Split-K factor, from measurements on MI355X (two of these workgroups fit a CU):
+//   * 192-256 workgroups already stream a [4096..6144, 4096] weight at its best rate, and every extra split adds an
+//     fp32 partial tile the consumer has to read back: take the smallest divisor of the stage count that reaches 192;
+//   * between 256 and ~450 workgroups some CUs get two and the others one, and the launch takes as long as with
+//     512 (320 workgroups on a [10240, 8192] weight: 46.7 us, 160 or 640: 43.5 us): skip those;
+//   * a K range left longer than 64 stages is cut further (a [8192, 28672] weight streams 22 % faster as 512
+//     workgroups of 56 stages than as 256 of 112).
 int gemm_skinny_pick_splits(int N, int K, int M) {
   const int tiles = (N + BN - 1) / BN * ((M + 63) / 64);
   const int KT = K / BK;
@@ -361,8 +365,10 @@ int gemm_skinny_pick_splits(int N, int K, int M) {
   for (int S = 1; S <= 16; ++S) {
     if (KT % S) continue;
     if (S > 1 && KT / S < 4) break;
+    const int wgs = tiles * S;
+    if (S > 1 && wgs > 256 && wgs < 450) continue;
     best = S;
-    if (tiles * S >= 192) break;
+    if (wgs >= 192 && (KT / S <= 64 || wgs >= 512)) break;
   }
   return best;
 }

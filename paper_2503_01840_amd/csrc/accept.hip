@@ -45,18 +45,13 @@ __global__ __launch_bounds__(256) void accept_stats_kernel(const float* __restri
 #pragma unroll
   for (int j = 0; j < 8; ++j)
     if (x[j] > mx) { mx = x[j]; am = idx[j]; }   // ascending index per thread: first maximum kept
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float ov = __shfl_xor(mx, o, 64);
-    const int oi = __shfl_xor(am, o, 64);
-    if (ov > mx || (ov == mx && oi < am)) { mx = ov; am = oi; }
-  }
+  wave_best_pair(mx, am);
   float sum = 0.f;
   if (mx > -INFINITY) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) sum += expf(x[j] - mx);   // exp(-inf) = 0 for the padding
   }
-  sum = wave_sum(sum);
+  sum = wave_sum_butterfly(sum);
   if (lane == 0) { redv[wave] = mx; redi[wave] = am; reds[wave] = sum; }
   __syncthreads();
   if (tid == 0) {
@@ -108,12 +103,7 @@ __global__ __launch_bounds__(64) void accept_walk_kernel(const float* __restrict
       const int i = __float_as_int(st[c * 4 + 1]);
       if (v > mx || (v == mx && i < am)) { mx = v; am = i; }
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const float ov = __shfl_xor(mx, o, 64);
-      const int oi = __shfl_xor(am, o, 64);
-      if (ov > mx || (ov == mx && oi < am)) { mx = ov; am = oi; }
-    }
+    wave_best_pair(mx, am);
     const unsigned long long kids = __ballot(lane < N && lane > cur && my_par == cur);
     if (greedy) {
       const unsigned long long hit = __ballot(lane < N && lane > cur && my_par == cur && my_tok == am);
@@ -129,7 +119,7 @@ __global__ __launch_bounds__(64) void accept_walk_kernel(const float* __restrict
     // ---- stochastic
     float tot = 0.f;
     for (int c = lane; c < n_chunks; c += 64) tot += st[c * 4 + 2] * expf(st[c * 4] - mx);
-    tot = wave_sum(tot);
+    tot = wave_sum_butterfly(tot);
     const float* z = logits + (size_t)row * V;
     float rej = 0.f;
     int n_struck = 0, accepted = -1;

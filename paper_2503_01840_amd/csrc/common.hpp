@@ -85,10 +85,56 @@ __device__ __forceinline__ float wave_sum(float v) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
   return v;
 }
+
+// Butterfly all-reduce over the 64 lanes without the LDS crossbar that __shfl_xor goes through (ds_bpermute,
+// ~100 clocks a step): step s hands every lane its own value and its partner's, in some order (a, b).  Steps 0, 1:
+// DPP quad permutes (lane ^ 1, lane ^ 2); 2, 3: DPP mirrors within 8 and within 16 lanes (once a group of 4 or 8
+// lanes agrees, the mirrored lane is as good a partner as lane ^ 4 or lane ^ 8); 4, 5: v_permlane16_swap and
+// v_permlane32_swap.  For commutative, idempotent-or-associative combiners every lane ends with the wavefront's result.
+template <int STEP>
+__device__ __forceinline__ void xlane_partners(uint32_t x, uint32_t& a, uint32_t& b) {
+  a = x;
+  if constexpr (STEP == 0) b = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0xB1, 0xF, 0xF, false);
+  else if constexpr (STEP == 1) b = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x4E, 0xF, 0xF, false);
+  else if constexpr (STEP == 2) b = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x141, 0xF, 0xF, false);
+  else if constexpr (STEP == 3) b = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x140, 0xF, 0xF, false);
+  else if constexpr (STEP == 4) { const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false); a = r[0]; b = r[1]; }
+  else { const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false); a = r[0]; b = r[1]; }
+}
+template <int STEP> __device__ __forceinline__ float xlane_max_step(float v) {
+  uint32_t a, b;
+  xlane_partners<STEP>(__float_as_uint(v), a, b);
+  return fmaxf(__uint_as_float(a), __uint_as_float(b));
+}
+template <int STEP> __device__ __forceinline__ float xlane_sum_step(float v) {
+  uint32_t a, b;
+  xlane_partners<STEP>(__float_as_uint(v), a, b);
+  return __uint_as_float(a) + __uint_as_float(b);
+}
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  v = xlane_max_step<0>(v); v = xlane_max_step<1>(v); v = xlane_max_step<2>(v);
+  v = xlane_max_step<3>(v); v = xlane_max_step<4>(v); v = xlane_max_step<5>(v);
   return v;
+}
+// same result on every lane; the summation order differs from wave_sum's (used where the last ulp is free)
+__device__ __forceinline__ float wave_sum_butterfly(float v) {
+  v = xlane_sum_step<0>(v); v = xlane_sum_step<1>(v); v = xlane_sum_step<2>(v);
+  v = xlane_sum_step<3>(v); v = xlane_sum_step<4>(v); v = xlane_sum_step<5>(v);
+  return v;
+}
+// (value, index) of the wavefront's best entry: larger value first, ties -> smaller index
+template <int STEP> __device__ __forceinline__ void xlane_best_step(float& v, int& i) {
+  uint32_t va, vb, ia, ib;
+  xlane_partners<STEP>(__float_as_uint(v), va, vb);
+  xlane_partners<STEP>((uint32_t)i, ia, ib);
+  const float fa = __uint_as_float(va), fb = __uint_as_float(vb);
+  const bool first = fa > fb || (fa == fb && (int)ia < (int)ib);
+  v = first ? fa : fb;
+  i = first ? (int)ia : (int)ib;
+}
+__device__ __forceinline__ void wave_best_pair(float& v, int& i) {
+  xlane_best_step<0>(v, i); xlane_best_step<1>(v, i); xlane_best_step<2>(v, i);
+  xlane_best_step<3>(v, i); xlane_best_step<4>(v, i); xlane_best_step<5>(v, i);
 }
 
 // Block-wide sum for blockDim.x a multiple of 64, <= 1024.  `red` is a __shared__ float[17].

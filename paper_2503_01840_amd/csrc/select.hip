@@ -14,12 +14,7 @@ struct ValIdx { float v; int i; };
 __device__ __forceinline__ bool better(float va, int ia, float vb, int ib) { return va > vb || (va == vb && ia < ib); }
 
 __device__ __forceinline__ ValIdx wave_best(ValIdx x) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float v = __shfl_xor(x.v, o, 64);
-    const int i = __shfl_xor(x.i, o, 64);
-    if (better(v, i, x.v, x.i)) { x.v = v; x.i = i; }
-  }
+  wave_best_pair(x.v, x.i);
   return x;
 }
 
@@ -63,7 +58,7 @@ __global__ __launch_bounds__(256) void topk_spans_kernel(const float* __restrict
   float sum = 0.f;
 #pragma unroll
   for (int j = 0; j < 8; ++j) sum += expf(v[j] - mx);  // exp(-inf) = 0 for the padding
-  sum = wave_sum(sum);
+  sum = wave_sum_butterfly(sum);
   const size_t o = (size_t)row * n_spans + span;
   if (lane == 0) { span_stat[2 * o] = mx; span_stat[2 * o + 1] = sum; }
   for (int r = 0; r < K; ++r) {
@@ -101,7 +96,7 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(const float* __restrict_
   mx = wave_max(mx);
   float sum = 0.f;
   for (int i = lane; i < n_spans; i += 64) sum += st[2 * i + 1] * expf(st[2 * i] - mx);
-  sum = wave_sum(sum);
+  sum = wave_sum_butterfly(sum);
   const float lse = logf(sum);
   const int C = n_spans * K;
   const float* cv = cand_val + (size_t)row * C;

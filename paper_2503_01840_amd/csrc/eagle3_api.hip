@@ -447,14 +447,14 @@ int eagle3_draft_expand(eagle3_ctx* ctx, const float* g_new, const int32_t* tok_
       pos = ctx->pos1; slot = ctx->slot; mask = ctx->mask; seq = ctx->seq;
       max_len = dkv->max_prefix_len + n_new;
       CK(launch_draft_input(ctx->bf16, ctx->tw.embed, c.vocab, tok_new, g_new, nullptr, M, k, ctx->dw.norm_embed,
-                            ctx->dw.norm_feat, c.rms_eps, ctx->act_k, ctx->x, st));
+                            ctx->dw.norm_feat, c.rms_eps, ctx->act_k, ctx->x, pos, d, c.rope_theta, ctx->cs, st));
     } else {
       pos = ds.row_pos; slot = ds.row_slot; mask = ds.row_mask; seq = ds.seq;
       max_len = dkv->max_prefix_len + n_new + (level - 1) * K;
       CK(launch_draft_input(ctx->bf16, ctx->tw.embed, c.vocab, ds.row_tok, ctx->a_buf, ds.row_src, M, k,
-                            ctx->dw.norm_embed, ctx->dw.norm_feat, c.rms_eps, ctx->act_k, ctx->x, st));
+                            ctx->dw.norm_embed, ctx->dw.norm_feat, c.rms_eps, ctx->act_k, ctx->x, pos, d, c.rope_theta, ctx->cs,
+                            st));
     }
-    CK(launch_rope_table(pos, M, d, c.rope_theta, ctx->cs, st));
     GemmWeights Wqkv = {{w.wq, w.wk, w.wv}, {H * d, Hkv * d, Hkv * d}, 3, 0};
     int S_qkv = 1, S_down = 1;
     TRY(ctx->project(ctx->act_k, Wqkv, M, (H + 2 * Hkv) * d, 2 * k, GEMM_EPI_PARTIAL, &S_qkv, st));

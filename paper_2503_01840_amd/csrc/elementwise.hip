@@ -117,12 +117,6 @@ __global__ __launch_bounds__(256) void tree_prep_kernel(const int32_t* __restric
   }
 }
 
-__global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restrict__ pos, int R, int d, float theta,
-                                                        float* __restrict__ cs) {
-  const int half = d / 2;
-  for (int e = blockIdx.x * 256 + threadIdx.x; e < R * half; e += gridDim.x * 256) rope_entry(cs, e / half, e % half, d, pos[e / half], theta);
-}
-
 // One workgroup per row; a thread handles four consecutive rotary pairs (i..i+3, i+d/2..i+d/2+3) of one head.
 template <bool BF16>
 __global__ __launch_bounds__(1024) void rope_kv_write_kernel(const float* __restrict__ qkv, int S, int R, int H, int Hkv,
@@ -198,7 +192,8 @@ __global__ __launch_bounds__(1024) void draft_input_kernel(const typename Act<BF
                                                           const typename Act<BF16>::type* __restrict__ g_embed,
                                                           const typename Act<BF16>::type* __restrict__ g_feat, float eps,
                                                           typename Act<BF16>::type* __restrict__ act,
-                                                          float* __restrict__ y) {
+                                                          float* __restrict__ y, const int32_t* __restrict__ pos,
+                                                          int head_dim, float theta, float* __restrict__ cs) {
   __shared__ float red_e[17], red_f[17];
   const int r = blockIdx.x;
   const int t = min(max(tok[r], 0), vocab - 1);
@@ -228,6 +223,8 @@ __global__ __launch_bounds__(1024) void draft_input_kernel(const typename Act<BF
       Act<BF16>::store4(act, r, k + c, 2 * k, v[j].x * iv * gf.x, v[j].y * iv * gf.y, v[j].z * iv * gf.z, v[j].w * iv * gf.w);
     }
   }
+  // the row's rotary table, for the q/k rotation that follows the projection
+  for (int i = threadIdx.x; i < head_dim / 2; i += blockDim.x) rope_entry(cs, r, i, head_dim, pos[r], theta);
 }
 
 __global__ __launch_bounds__(64) void draft_prep1_kernel(const int32_t* __restrict__ kv_indptr,
@@ -286,12 +283,6 @@ hipError_t launch_tree_prep(const int32_t* parent, const int32_t* kv_indptr, con
   return hipGetLastError();
 }
 
-hipError_t launch_rope_table(const int32_t* pos, int R, int head_dim, float theta, float* cs, hipStream_t st) {
-  const int blocks = (R * head_dim / 2 + 255) / 256;
-  hipLaunchKernelGGL(rope_table_kernel, dim3(blocks), dim3(256), 0, st, pos, R, head_dim, theta, cs);
-  return hipGetLastError();
-}
-
 hipError_t launch_rope_kv_write(bool bf16, const float* qkv_partial, int S, int R, int H, int Hkv, int d, const float* cs,
                                 const int32_t* slot, void* q, void* kcache, void* vcache, hipStream_t st) {
   if (d % 8) return hipErrorInvalidValue;
@@ -325,15 +316,15 @@ hipError_t launch_reduce_partials(const float* partial, int S, int M, int N, flo
 
 hipError_t launch_draft_input(bool bf16, const void* embed, int vocab, const int32_t* tok, const float* feat,
                               const int32_t* src_row, int M, int k, const void* g_embed, const void* g_feat, float eps,
-                              void* act, float* y, hipStream_t st) {
+                              void* act, float* y, const int32_t* pos, int head_dim, float theta, float* cs, hipStream_t st) {
   if (k % 4 || k > 16384) return hipErrorInvalidValue;
   const int threads = std::min(1024, ((k / 4 + 63) / 64) * 64);
   if (bf16)
     hipLaunchKernelGGL(draft_input_kernel<true>, dim3(M), dim3(threads), 0, st, (const bf16_t*)embed, vocab, tok, feat,
-                       src_row, k, (const bf16_t*)g_embed, (const bf16_t*)g_feat, eps, (bf16_t*)act, y);
+                       src_row, k, (const bf16_t*)g_embed, (const bf16_t*)g_feat, eps, (bf16_t*)act, y, pos, head_dim, theta, cs);
   else
     hipLaunchKernelGGL(draft_input_kernel<false>, dim3(M), dim3(threads), 0, st, (const float*)embed, vocab, tok, feat,
-                       src_row, k, (const float*)g_embed, (const float*)g_feat, eps, (float*)act, y);
+                       src_row, k, (const float*)g_embed, (const float*)g_feat, eps, (float*)act, y, pos, head_dim, theta, cs);
   return hipGetLastError();
 }
 

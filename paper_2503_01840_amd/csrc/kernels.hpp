@@ -55,8 +55,6 @@ hipError_t launch_add_norm(bool bf16, float* x, const float* partial, int S, int
 hipError_t launch_tree_prep(const int32_t* parent, const int32_t* kv_indptr, const int32_t* prefix_len, int B, int N,
                             int head_dim, float theta, int32_t* depth, uint32_t* mask, int32_t* slot, float* cs,
                             SeqInfo* seq, hipStream_t st);
-// Rotary tables for rows whose positions are already on the device.
-hipError_t launch_rope_table(const int32_t* pos, int R, int head_dim, float theta, float* cs, hipStream_t st);
 // Sums the q|k|v split-K partials, rotates q and k, writes q (activation type, [R,H,d]) and the cache rows.
 hipError_t launch_rope_kv_write(bool bf16, const float* qkv_partial, int S, int R, int H, int Hkv, int d, const float* cs,
                                 const int32_t* slot, void* q, void* kcache, void* vcache, hipStream_t st);
@@ -64,10 +62,11 @@ hipError_t launch_swiglu_f32(const float* gu, int R, int I, float* h, hipStream_
 hipError_t launch_pack3(bool bf16, const float* a, const float* b, const float* c, int M, int k, void* act, hipStream_t st);
 hipError_t launch_reduce_partials(const float* partial, int S, int M, int N, float* out, hipStream_t st);
 // Draft layer input: act[r] = [RMSNorm(E[tok[r]]; g_embed) ; RMSNorm(f_r; g_feat)], y[r] = f_r,
-// with f_r = feat[src_row ? src_row[r] : r].
+// with f_r = feat[src_row ? src_row[r] : r]; also the rotary table cs[r] of position pos[r] (positions already on
+// the device).
 hipError_t launch_draft_input(bool bf16, const void* embed, int vocab, const int32_t* tok, const float* feat,
                               const int32_t* src_row, int M, int k, const void* g_embed, const void* g_feat, float eps,
-                              void* act, float* y, hipStream_t st);
+                              void* act, float* y, const int32_t* pos, int head_dim, float theta, float* cs, hipStream_t st);
 // Rows of draft forward 1: positions, slots, causal masks, sequence info.
 hipError_t launch_draft_prep1(const int32_t* kv_indptr, const int32_t* prefix_len, int n_new, int32_t* pos, int32_t* slot,
                               uint32_t* mask, SeqInfo* seq, hipStream_t st);

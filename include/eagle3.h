@@ -190,6 +190,19 @@ int eagle3_accept(eagle3_ctx* ctx, int32_t B, int32_t N, const float* logits, co
                   const int32_t* parent, float temperature, const float* uniforms,
                   int32_t* accept_len, int32_t* path, int32_t* bonus_tok, eagle3_stream stream);
 
+/* For callers that cannot allocate device memory and hold no context: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  The same acceptance walk as eagle3_accept (same kernels, same
+ * results) with its per-(row, 2048-logit chunk) statistics kept in a fixed 1 MiB device array inside the library
+ * instead of a workspace: no eagle3_ctx, no workspace, no allocation of any kind.
+ *   Limits: 1 <= N <= 64 and B*N * ceil(vocab / 2048) <= 65536 (e.g. 1040 rows at vocab 128256); beyond that the
+ *   call returns EAGLE3_E_SHAPE and enqueues nothing.
+ *   The array is per GPU (the device current at the call must be the stream's device) and is shared by every call
+ *   on that GPU: calls that overlap in time on one GPU race on it; calls on one stream are safe back to back.
+ *   Nothing in it needs clearing between calls (every entry a call reads it has written itself). */
+int eagle3_accept_static(int32_t B, int32_t N, int32_t vocab, const float* logits, const int32_t* tree_tok,
+                         const int32_t* parent, float temperature, const float* uniforms,
+                         int32_t* accept_len, int32_t* path, int32_t* bonus_tok, eagle3_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,7 +17,7 @@ EAGLE3_FP32, EAGLE3_BF16 = 0, 1
 EXPORTS = ["eagle3_create", "eagle3_destroy", "eagle3_workspace_bytes", "eagle3_set_workspace", "eagle3_set_weights",
            "eagle3_strerror", "eagle3_last_error", "eagle3_profile_begin", "eagle3_profile_read", "eagle3_profile_end",
            "eagle3_fuse_features", "eagle3_draft_expand",
-           "eagle3_tree_verify", "eagle3_tree_verify_layers", "eagle3_accept"]
+           "eagle3_tree_verify", "eagle3_tree_verify_layers", "eagle3_accept", "eagle3_accept_static"]
 
 
 class Config(C.Structure):
@@ -83,6 +83,8 @@ def lib():
                                                 C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.eagle3_accept.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.eagle3_accept_static.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -279,4 +281,20 @@ def eagle3_accept(ctx, logits, tree_tok, parent, temperature=0.0, uniforms=None)
                                _ptr(parent, torch.int32), float(temperature),
                                _ptr(uniforms, torch.float32) if uniforms is not None else None, _ptr(accept_len),
                                _ptr(path), _ptr(bonus), _stream()))
+    return accept_len, path, bonus
+
+
+def eagle3_accept_static(logits, tree_tok, parent, temperature=0.0, uniforms=None, out=None):
+    """eagle3_accept without a context or workspace (fixed scratch inside the library).  `out` = preallocated
+    (accept_len, path, bonus) to make the call allocation-free on the torch side as well."""
+    B, N = tree_tok.shape
+    dev = tree_tok.device
+    if out is None:
+        out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, N, dtype=torch.int32, device=dev),
+               torch.empty(B, dtype=torch.int32, device=dev))
+    accept_len, path, bonus = out
+    _check(lib().eagle3_accept_static(B, N, logits.shape[-1], _ptr(logits, torch.float32), _ptr(tree_tok, torch.int32),
+                                      _ptr(parent, torch.int32), float(temperature),
+                                      _ptr(uniforms, torch.float32) if uniforms is not None else None, _ptr(accept_len),
+                                      _ptr(path), _ptr(bonus), _stream()))
     return accept_len, path, bonus

@@ -8,6 +8,9 @@
 // The walk touches only the statistics of the visited rows plus, for the bonus draw, one chunk of logits.
 #include <limits.h>
 
+#include <mutex>
+
+#include "../../include/eagle3.h"
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -236,4 +239,53 @@ hipError_t launch_accept(const float* logits, const int32_t* tree_tok, const int
   hipLaunchKernelGGL(accept_walk_kernel, dim3(B), dim3(64), 0, st, logits, tree_tok, parent, N, V, n_chunks, inv_t, greedy,
                      uniforms, scratch, accept_len, path, bonus);
   return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// The same walk for callers that cannot allocate and hold no context (code under HIP graph capture, tight serving
+// loops): the per-(row, chunk) statistics live in a fixed device array of this library instead of a workspace.
+// Each GPU holds its own copy of the array at its own address; the address is looked up once per device, with that
+// device current, and only that pointer (never the array's name) is handed to the kernels.
+#define ACCEPT_STATIC_FLOATS (256 * 1024)                    /* 1 MiB: rows * chunks <= 65536 */
+static __device__ __align__(256) float scratch[ACCEPT_STATIC_FLOATS];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_static_mu;
+float* g_static_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+hipError_t static_scratch(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_static_ptr[dev] = (float*)p;
+  }
+  *out = g_static_ptr[dev];
+  return hipSuccess;
+}
+}  // namespace
+
+extern "C" int eagle3_accept_static(int32_t B, int32_t N, int32_t vocab, const float* logits, const int32_t* tree_tok,
+                                    const int32_t* parent, float temperature, const float* uniforms, int32_t* accept_len,
+                                    int32_t* path, int32_t* bonus_tok, eagle3_stream stream) {
+  if (!logits || !tree_tok || !parent || !accept_len || !path || !bonus_tok) return EAGLE3_E_NULL;
+  if (temperature > 0.f && !uniforms) return EAGLE3_E_NULL;
+  if (B < 1 || N < 1 || N > 64 || vocab < 1 || !(temperature >= 0.f)) return EAGLE3_E_SHAPE;
+  if ((size_t)B * N > (size_t)ACCEPT_STATIC_FLOATS) return EAGLE3_E_SHAPE;
+  if (accept_scratch_floats(B * N, vocab) > (size_t)ACCEPT_STATIC_FLOATS) return EAGLE3_E_SHAPE;
+  float* ptr = nullptr;
+  if (static_scratch(&ptr) != hipSuccess) return EAGLE3_E_HIP;
+  // every (row, chunk) entry the walk reads is written by the statistics pass of the same call: nothing to clear
+  if (launch_accept(logits, tree_tok, parent, B, N, vocab, temperature, uniforms, ptr, accept_len, path, bonus_tok,
+                    (hipStream_t)stream) != hipSuccess)
+    return EAGLE3_E_HIP;
+  return EAGLE3_OK;
 }

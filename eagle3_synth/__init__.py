@@ -9,5 +9,5 @@ and the GPU path's tests may draw the same bits from it.
 from .configs import Eagle3Shape, SHAPES, get_shape  # noqa: F401
 from .inputs import (  # noqa: F401
     SEED, normal, uniform01, uniform_ints, make_d2t, TensorIds,
-    layer_weights, target_globals, draft_weights, kv_layer, random_tree, chain_tree, ragged_batch,
+    layer_weights, target_globals, draft_weights, kv_layer, random_tree, reorder_tree, chain_tree, ragged_batch,
 )

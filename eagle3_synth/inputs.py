@@ -226,6 +226,33 @@ def random_tree(seed, salt, n_nodes, max_depth, max_children):
     return parent, depth
 
 
+def reorder_tree(parent, order="dfs", seed=SEED):
+    """The same rooted tree with its nodes renumbered: "dfs" = depth-first pre-order (a child directly follows
+    its parent's earlier subtrees, depths go up and down along the node ids), "mixed" = a seeded random order
+    that only keeps every parent before its children.  Returns (parent[int32, N], old id of every new node)."""
+    parent = np.asarray(parent)
+    n = len(parent)
+    kids = [[] for _ in range(n)]
+    for i in range(1, n):
+        kids[int(parent[i])].append(i)
+    if order == "dfs":
+        seq, stack = [], [0]
+        while stack:
+            u = stack.pop()
+            seq.append(u)
+            stack.extend(reversed(kids[u]))
+    else:
+        rs = np.random.RandomState(seed % (2 ** 31 - 1))
+        seq, ready = [], [0]
+        while ready:
+            u = ready.pop(rs.randint(len(ready)))
+            seq.append(u)
+            ready.extend(kids[u])
+    new_id = {old: new for new, old in enumerate(seq)}
+    new_parent = np.array([-1 if parent[o] < 0 else new_id[int(parent[o])] for o in seq], dtype=np.int32)
+    return new_parent, np.array(seq, dtype=np.int32)
+
+
 def chain_tree(n_nodes):
     parent = np.arange(-1, n_nodes - 1, dtype=np.int32)
     return parent, np.arange(n_nodes, dtype=np.int32)

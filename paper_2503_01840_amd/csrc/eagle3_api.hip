@@ -122,7 +122,7 @@ struct eagle3_ctx {
     }
     if (bf16) {
       int S = epi == GEMM_EPI_SWIGLU ? 1 : gemm_skinny_pick_splits(N, K, M);
-      while (S > 1 && (size_t)S * M * N > part_floats) S /= 2;
+      while (S > 1 && ((size_t)S * M * N > part_floats || (K / 128) % S != 0)) --S;   // the next smaller divisor of the stage count
       if (epi == GEMM_EPI_PARTIAL && direct_out == nullptr && (size_t)S * M * N > part_floats) return EAGLE3_E_STATE;
       void* out = epi == GEMM_EPI_SWIGLU ? act_h : (direct_out && S == 1 ? (void*)direct_out : (void*)part);
       Stamp* sp = profiling && stamps_used < stamps.size() ? &stamps[stamps_used++] : nullptr;
@@ -173,7 +173,8 @@ int eagle3_create(const eagle3_config* cfg, eagle3_ctx** out) {
     return EAGLE3_E_SHAPE;
   if (c.dtype != EAGLE3_BF16 && c.dtype != EAGLE3_FP32) return EAGLE3_E_SHAPE;
   if (c.max_batch < 1 || c.max_nodes < 1 || c.max_nodes > 64 || c.max_depth < 1 || c.max_topk < 1 || c.max_topk > 16 ||
-      c.max_new < 1 || c.max_new > 64 || (c.max_depth - 1) * c.max_topk > 128)
+      c.max_new < 1 || c.max_new > 64 || (c.max_depth - 1) * c.max_topk > 128 ||
+      1 + c.max_topk + (c.max_depth - 1) * c.max_topk * c.max_topk > DRAFT_MAX_POOL)
     return EAGLE3_E_SHAPE;
   for (int t = 0; t < 3; ++t)
     if (c.tap_layers[t] < 0 || c.tap_layers[t] >= c.n_layers) return EAGLE3_E_SHAPE;

@@ -34,9 +34,15 @@ __global__ __launch_bounds__(1024) void add_norm_kernel(float* __restrict__ x, c
     const int v = threadIdx.x + j * bd;
     if (v < nvec) {
       float4 a = *(const float4*)(x + (size_t)r * k + 4 * v);
-      for (int s = 0; s < S; ++s) {
-        const float4 p = *(const float4*)(partial + ((size_t)s * R + r) * k + 4 * v);
-        a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+      // four partial sums per round, all requested before the first is added (one memory round trip per round
+      // instead of one per partial sum); the order of the additions stays s = 0, 1, 2, ...
+      for (int s0 = 0; s0 < S; s0 += 4) {
+        float4 p[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) p[i] = *(const float4*)(partial + ((size_t)min(s0 + i, S - 1) * R + r) * k + 4 * v);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (s0 + i < S) { a.x += p[i].x; a.y += p[i].y; a.z += p[i].z; a.w += p[i].w; }
       }
       *(float4*)(x + (size_t)r * k + 4 * v) = a;
 #pragma unroll
@@ -46,17 +52,23 @@ __global__ __launch_bounds__(1024) void add_norm_kernel(float* __restrict__ x, c
       val[j] = a;
     }
   }
+  float4 g[VPT];                                      // requested before the reduction, used after it
+  if (act != nullptr) {
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+      const int v = threadIdx.x + j * bd;
+      if (v < nvec) g[j] = load4_f32(gain, 4 * v);
+    }
+  }
   ss = block_sum(ss, red);
   if (act == nullptr) return;
   const float inv = 1.0f / sqrtf(ss / (float)k + eps);
 #pragma unroll
   for (int j = 0; j < VPT; ++j) {
     const int v = threadIdx.x + j * bd;
-    if (v < nvec) {
-      const float4 g = load4_f32(gain, 4 * v);
-      Act<BF16>::store4(act, r, 4 * v, k, val[j].x * inv * g.x, val[j].y * inv * g.y, val[j].z * inv * g.z,
-                        val[j].w * inv * g.w);
-    }
+    if (v < nvec)
+      Act<BF16>::store4(act, r, 4 * v, k, val[j].x * inv * g[j].x, val[j].y * inv * g[j].y, val[j].z * inv * g[j].z,
+                        val[j].w * inv * g[j].w);
   }
 }
 
@@ -131,11 +143,20 @@ __global__ __launch_bounds__(1024) void rope_kv_write_kernel(const float* __rest
   for (int e = threadIdx.x; e < (H + 2 * Hkv) * q4; e += blockDim.x) {
     const int h = e / q4, i = (e % q4) * 4;
     float4 x1 = make_float4(0.f, 0.f, 0.f, 0.f), x2 = x1;
-    for (int s = 0; s < S; ++s) {
-      const float* row = qkv + ((size_t)s * R + r) * NT + h * d;
-      const float4 a = *(const float4*)(row + i), b = *(const float4*)(row + i + half);
-      x1.x += a.x; x1.y += a.y; x1.z += a.z; x1.w += a.w;
-      x2.x += b.x; x2.y += b.y; x2.z += b.z; x2.w += b.w;
+    for (int s0 = 0; s0 < S; s0 += 4) {                 // four partial sums per memory round trip, added in order
+      float4 a[4], b[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float* row = qkv + ((size_t)min(s0 + j, S - 1) * R + r) * NT + h * d;
+        a[j] = *(const float4*)(row + i);
+        b[j] = *(const float4*)(row + i + half);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (s0 + j < S) {
+          x1.x += a[j].x; x1.y += a[j].y; x1.z += a[j].z; x1.w += a[j].w;
+          x2.x += b[j].x; x2.y += b[j].y; x2.z += b[j].z; x2.w += b[j].w;
+        }
     }
     T* dst;
     if (h < H + Hkv) {

@@ -83,6 +83,7 @@ hipError_t launch_tree_attention(bool bf16, const void* q, const void* kcache, c
                                  int n_splits, float* scratch, void* out, hipStream_t st);
 
 // ---------------------------------------------------------------- draft tree (select.hip)
+#define DRAFT_MAX_POOL 2048   /* candidates the final rerank can hold: 1 + K + (D-1) K^2 must not exceed it */
 struct DraftState {          // device arrays owned by the workspace
   int32_t* pool_tok;         // [pool] draft ids
   int32_t* pool_parent;      // [pool]

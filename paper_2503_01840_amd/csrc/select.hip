@@ -201,7 +201,7 @@ __global__ __launch_bounds__(256) void draft_select_kernel(DraftState s, const i
   }
 }
 
-constexpr int MAX_POOL = 2048;
+constexpr int MAX_POOL = DRAFT_MAX_POOL;
 
 __global__ __launch_bounds__(1024) void draft_rerank_kernel(DraftState s, const int32_t* __restrict__ d2t,
                                                            const int32_t* __restrict__ tok_new, int n_new, int pool,

@@ -8,11 +8,26 @@ import eagle3_synth as S
 from oracle import eagle3_oracle as O
 
 
+class LazyEmbedRows:
+    """Rows of the seeded embedding table, generated when indexed (the full 128256 x 8192 table is never built)."""
+
+    def __init__(self, shape, seed=S.SEED):
+        self.shape, self.seed = shape, seed
+
+    def __getitem__(self, idx):
+        k = self.shape.hidden
+        dt = torch.float32 if self.shape.dtype == "fp32" else torch.bfloat16
+        rows = [O.as_f64(S.normal(self.seed, S.TensorIds.EMBED, (k,), 0.02, 0.0, dt, start=int(t) * k))
+                for t in np.asarray(idx).reshape(-1)]
+        return np.stack(rows).reshape(tuple(np.shape(idx)) + (k,))
+
+
 class OracleModel:
     """Float64 weights of a shape; target layers are generated on demand (and cached when small)."""
 
-    def __init__(self, shape, seed=S.SEED, cache_layers=None):
+    def __init__(self, shape, seed=S.SEED, cache_layers=None, lazy_embed=False):
         self.shape, self.seed = shape, seed
+        self.lazy_embed = lazy_embed
         self.rounding = "bf16" if shape.dtype == "bf16" else "none"
         self._cache = {} if (cache_layers if cache_layers is not None else shape.layer_params() * shape.n_layers < 3e8) else None
         self.tg = None
@@ -30,6 +45,9 @@ class OracleModel:
         if self.tg is None:
             self.tg = O.weights_f64(S.target_globals(self.shape, self.seed))
         return self.tg
+
+    def embed(self):
+        return LazyEmbedRows(self.shape, self.seed) if self.lazy_embed else self.globals()["embed"]
 
     def draft(self):
         if self.dw is None:
@@ -81,7 +99,7 @@ def oracle_draft(shape, model, inp, depth, topk, n_nodes, follow=None, tol=1e-2)
     cap = n_ctx + inp["n_new"] + (depth - 1) * topk
     Kc = np.zeros((cap, shape.n_kv_heads, shape.head_dim)); Vc = np.zeros_like(Kc)
     Kc[:n_ctx], Vc[:n_ctx] = O.as_f64(Kd), O.as_f64(Vd)
-    out = O.draft_expand(shape, model.draft(), model.globals()["embed"], O.as_f64(inp["g_new"]),
+    out = O.draft_expand(shape, model.draft(), model.embed(), O.as_f64(inp["g_new"]),
                          inp["tok_new"].numpy().astype(np.int64), Kc, Vc, n_ctx, depth, topk, n_nodes,
                          rounding=model.rounding, follow=follow, tol=tol)
     out["K_cache"], out["V_cache"] = Kc, Vc

@@ -1,17 +1,22 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
-Tolerances (bf16 configurations).  Logits: 2e-2 max-abs.  Residual stream / taps: 2e-2 in units of the
-stream's RMS (the synthetic stack's stream grows from 0.02 to ~14 RMS over 32 layers; max-abs 2e-2 is kept
-for O(1) streams).  These hold for every SINGLE layer given the same input (teacher-forced tests below, full
-8B / 70B shapes).  Through a deep stack two correct bf16 implementations drift apart: an input difference of
-1e-6 relative flips the bf16 rounding of ~0.03 % of the activations by one ulp (2^-8 relative), the flips
-act as fresh rounding noise, and after two layers the roundings of the two runs are uncorrelated.  The
-oracle measures that drift itself: tests/golden stores its result with and without activation rounding, and
-the end-to-end tests require  |GPU - oracle_bf16| <= 2 * max|oracle_bf16 - oracle_exact|  (+2e-2),
-plus identical argmax wherever the oracle's top-1 margin exceeds that bound.
+Tolerances (bf16 configurations).  A SINGLE layer given the same input on both sides holds logits to 2e-2 max-abs
+and the residual stream / taps to 2e-2 in units of the stream's RMS (teacher-forced tests below and in
+test_gpu_shapes.py, full 8B / 70B shapes, every element).  Through a deep stack two correct implementations that
+round to bf16 at the same places still drift apart: a last-bit difference before a rounding flips that rounding now
+and then, and the synthetic random-weight stack amplifies every flip.  The ORACLE measures that drift on itself:
+tests/golden stores, beside its bf16-mode result, statistics of two more oracle runs: "drift_in" (rows entering
+layer 0 perturbed by 1e-7 relative) and "drift_all" (relative noise of 2^-20, the size of fp32 accumulation error,
+on every value right before each bf16 rounding).  The end-to-end tests require, per checked layer, for the taps and
+for the logits,
+    RMS(GPU - oracle) <= 1.5 * RMS drift_all      and      max|GPU - oracle| <= 2 * max drift_all
+(never tighter than the single-layer tolerance), identical arg-max wherever the oracle's top-1 margin exceeds the max
+bound, and they print the measured figures (collected in profiles/parity_errors.txt).  The draft's cumulative scores
+and near-tie margin are bounded the same way by the stored per-level score drift.
 
-c2 (one 8B-shaped layer + LM head, draft depth 6) runs the oracle online.  c3 / c4 / c5 use the stored
-samples (the full fp64 forward takes minutes to half an hour of CPU).
+c2 (one 8B-shaped layer + LM head, draft depth 6) runs the oracle online.  c3 / c4 / c5 compare with the stored
+oracle outputs: residual stream after selected layers and the taps in full (every row and column), logits at 2048
+seeded vocabulary entries per row plus the 64 largest and the log-sum-exp.
 """
 import os
 
@@ -25,13 +30,8 @@ import pipeline as PL
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
-TOL = 2e-2
-# Draft scores are sums of up to D log-probabilities, each carrying the single-layer logit error (<= 2e-2,
-# ~5e-3 typical): selections closer than this are near-ties that the oracle follows and checks.
-DRAFT_TOL = 4e-2
-
-
+from parity import (MAX_FACTOR, RMS_FACTOR, TOL, bounded as _bounded, check_scores as _check_scores,
+                    draft_tolerances as _draft_tolerances, golden as _golden, report as _report, rms as _rms)
 def _E():
     import paper_2503_01840_amd as E
     return E
@@ -54,41 +54,27 @@ def _stream_close(got, ref, what=""):
     assert err < TOL * scale, f"{what}: max err {err:.4f} > {TOL * scale:.4f}"
 
 
-def _check_sampled(g, prefix, logits, taps, hidden):
-    """End-to-end comparison through a deep stack against the stored oracle samples (see module docstring)."""
-    vsel, csel, hl = g["vsel"], g["csel"], g["hidden_layers"]
-    ex = prefix + "exact_"
-    report = []
+def _check_stored(tag, g, prefix, logits, taps, hidden):
+    """End-to-end comparison through a deep stack against the stored oracle outputs (see the module docstring)."""
+    hl = g["hidden_layers"]
     for i, l in enumerate(hl):
-        ref, exact = g[prefix + "hidden_at"][i], g[ex + "hidden_at"][i]
-        budget = 2.0 * float(np.max(np.abs(ref - exact))) + TOL
-        err = float(np.max(np.abs(hidden[l][:, csel] - ref)))
-        report.append(f"layer {l - 1}: err {err:.4f} budget {budget:.4f}")
-        assert err <= budget, report[-1]
+        ref = g[prefix + "hidden"][i].astype(np.float64)
+        _bounded(f"{tag} residual stream after layer {int(l) - 1}", hidden[l], ref, g[prefix + "drift_all_hidden"][i],
+                 max(1.0, _rms(ref)))
     for t in range(3):
-        ref, exact = g[prefix + "taps_at"][t], g[ex + "taps_at"][t]
-        assert np.max(np.abs(taps[t][:, csel] - ref)) <= 2.0 * np.max(np.abs(ref - exact)) + TOL
-    ref, exact = g[prefix + "logits_at"], g[ex + "logits_at"]
-    lbudget = 2.0 * float(np.max(np.abs(ref - exact))) + TOL
-    lerr = float(np.max(np.abs(logits[:, vsel] - ref)))
-    report.append(f"logits: err {lerr:.4f} budget {lbudget:.4f}")
-    assert lerr <= lbudget, report[-1]
-    top_idx, top_val = g[prefix + "top5_idx"], g[prefix + "top5_val"]
-    got_top = np.take_along_axis(logits, top_idx.astype(np.int64), 1)
-    assert np.max(np.abs(got_top - top_val)) <= lbudget
-    clear = (top_val[:, 0] - top_val[:, 1]) > 2 * lbudget
+        ref = g[prefix + "taps"][t].astype(np.float64)
+        _bounded(f"{tag} tap {t}", taps[t], ref, g[prefix + "drift_all_taps"][t], max(1.0, _rms(ref)))
+    vsel = g[prefix + "vsel"].astype(np.int64)
+    drift = g[prefix + "drift_all_logits"]
+    lbound = _bounded(f"{tag} logits ({vsel.shape[1]} sampled entries per row)", np.take_along_axis(logits, vsel, 1),
+                      g[prefix + "logits_at"].astype(np.float64), drift)
+    top_idx, top_val = g[prefix + "top_idx"].astype(np.int64), g[prefix + "top_val"].astype(np.float64)
+    _bounded(f"{tag} logits ({top_idx.shape[1]} largest per row)", np.take_along_axis(logits, top_idx, 1), top_val, drift)
+    clear = (top_val[:, 0] - top_val[:, 1]) > 2 * lbound
     assert np.array_equal(np.argmax(logits, 1)[clear], top_idx[clear, 0])
     lse = np.log(np.sum(np.exp(logits - logits.max(1, keepdims=True)), 1)) + logits.max(1)
-    assert np.max(np.abs(lse - g[prefix + "logsumexp"])) <= lbudget
-    print("; ".join(report))
-
-
-def _check_scores(got, ref):
-    """Cumulative log-probabilities: every level adds one log-softmax value with the single-forward logit
-    error, so an entry at level d is allowed d * 1e-2."""
-    lvl = np.maximum(ref["pool_depth"], 1)
-    assert np.all(np.abs(got["pool_score"] - ref["pool_score"]) <= 1e-2 * lvl)
-    assert np.all(np.abs(got["score"] - ref["score"]) <= 1e-2 * np.maximum(ref["depth"], 1))
+    assert np.max(np.abs(lse - g[prefix + "logsumexp"])) <= lbound
+    _report(f"{tag}: arg-max compared on {int(clear.sum())} of {len(clear)} rows (top-1 margin > {2 * lbound:.3f})")
 
 
 def test_c2_draft_and_verify_online_oracle():
@@ -103,14 +89,15 @@ def test_c2_draft_and_verify_online_oracle():
                                 D, K, N, debug=True)
     torch.cuda.synchronize()
     got = {k: v.cpu().numpy() for k, v in got.items()}
-    ref = PL.oracle_draft(shape, model, inp, D, K, N, tol=DRAFT_TOL,
+    g = _golden("c2")
+    tie_tol, level_tol = _draft_tolerances(g, D)
+    ref = PL.oracle_draft(shape, model, inp, D, K, N, tol=tie_tol,
                           follow={"pool_tok": got["pool_tok"], "frontier": got["frontier"], "chosen": got["chosen"]})
-    print(f"c2 draft: min selection gap {ref['min_gap']:.2e}, near-ties followed {ref['n_followed']}")
-    if ref["min_gap"] > DRAFT_TOL:
+    if ref["min_gap"] > tie_tol:
         assert ref["n_followed"] == 0
     for key in ("tree_tok", "parent", "depth", "chosen"):
         assert np.array_equal(got[key], ref[key]), key
-    _check_scores(got, ref)
+    _check_scores("c2", got, ref, level_tol)
     # verification of the oracle's tree: one layer + LM head against a 2048-token cache
     vref = PL.oracle_verify(shape, model, inp, ref["tree_tok"], ref["parent"], keep_hidden=True)
     pairs = [PL.target_kv_cpu(shape, inp, 0)]
@@ -124,9 +111,9 @@ def test_c2_draft_and_verify_online_oracle():
     for t in range(3):
         _stream_close(taps[t, 0].cpu().numpy(), vref["taps"][t], f"tap {t}")
     lg = logits[0].cpu().numpy()
-    lerr = float(np.max(np.abs(lg - vref["logits"])))
-    print(f"c2 logits: max err {lerr:.5f} over {lg.size} entries, rms {float(np.sqrt(np.mean((lg - vref['logits']) ** 2))):.5f}")
-    assert lerr < TOL
+    # one layer + LM head: the plain 2e-2 is where the oracle's own self-drift already sits (stored: max 0.03 over the
+    # 7.7 M logits for fp32-sized noise, 0.025 for a 1e-7 input perturbation), so the bound is the drift multiple
+    _bounded("c2 logits (every entry)", lg, vref["logits"], g["drift_all_logits"])
     srt = np.sort(vref["logits"], 1)
     clear = (srt[:, -1] - srt[:, -2]) > 1e-2
     assert np.array_equal(np.argmax(lg, 1)[clear], np.argmax(vref["logits"], 1)[clear])
@@ -146,19 +133,12 @@ def test_c3_draft_online_oracle_follows_near_ties():
                                 D, K, N, debug=True)
     torch.cuda.synchronize()
     got = {k: v.cpu().numpy() for k, v in got.items()}
-    ref = PL.oracle_draft(shape, model, inp, D, K, N, tol=DRAFT_TOL,
+    tie_tol, level_tol = _draft_tolerances(_golden("c3"), D)
+    ref = PL.oracle_draft(shape, model, inp, D, K, N, tol=tie_tol,
                           follow={"pool_tok": got["pool_tok"], "frontier": got["frontier"], "chosen": got["chosen"]})
-    print(f"c3 draft: min selection gap {ref['min_gap']:.2e}, near-ties followed {ref['n_followed']}")
     for key in ("tree_tok", "parent", "depth", "chosen"):
         assert np.array_equal(got[key], ref[key]), key
-    _check_scores(got, ref)
-
-
-def _golden(name):
-    path = os.path.join(GOLD, f"{name}_verify.npz")
-    if not os.path.exists(path):
-        pytest.skip(f"{path} not generated (python tests/golden/make_golden.py {name})")
-    return np.load(path)
+    _check_scores("c3", got, ref, level_tol)
 
 
 @pytest.mark.parametrize("name", ["c3", "c5"])
@@ -175,7 +155,7 @@ def test_full_depth_verify_against_stored_oracle_samples(name):
     pp = torch.as_tensor(g["parent"], dtype=torch.int32, device=DEV)[None]
     logits, taps, hidden = E.eagle3_tree_verify(ctx, tt, pp, kv, want_hidden=True)
     torch.cuda.synchronize()
-    _check_sampled(g, "", logits[0].cpu().numpy(), taps[:, 0].cpu().numpy(), hidden[:, 0].cpu().numpy())
+    _check_stored(name, g, "", logits[0].cpu().numpy(), taps[:, 0].cpu().numpy(), hidden[:, 0].cpu().numpy())
 
 
 def test_c4_ragged_batch64_verify_against_stored_oracle_samples():
@@ -193,7 +173,7 @@ def test_c4_ragged_batch64_verify_against_stored_oracle_samples():
                                                 torch.as_tensor(rb["parent"], device=DEV), kv, want_hidden=True)
     torch.cuda.synchronize()
     for b in g["seqs"]:
-        _check_sampled(g, f"s{b}_", logits[b].cpu().numpy(), taps[:, b].cpu().numpy(), hidden[:, b].cpu().numpy())
+        _check_stored(f"c4 sequence {b}", g, f"s{b}_", logits[b].cpu().numpy(), taps[:, b].cpu().numpy(), hidden[:, b].cpu().numpy())
     # per-sequence independence: every sequence of the batch gives finite logits, and a second run is bit-identical
     assert torch.isfinite(logits).all()
     logits2, _ = E.eagle3_tree_verify(ctx, torch.as_tensor(rb["tree_tok"], device=DEV), torch.as_tensor(rb["parent"], device=DEV), kv)

@@ -1,0 +1,210 @@
+"""GPU parity at shapes and orderings the other files do not reach: feature fusion and drafting at the 8B / 70B
+shapes, node orders other than level order, one teacher-forced layer of the batched configuration at 384 and 512
+rows (every row and column), and a whole step chained on the library's own outputs."""
+import numpy as np
+import pytest
+import torch
+
+import eagle3_synth as S
+from oracle import eagle3_oracle as O
+import parity
+import pipeline as PL
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL = 2e-2
+
+
+def _E():
+    import paper_2503_01840_amd as E
+    return E
+
+
+def _rms(a):
+    return float(np.sqrt(np.mean(np.square(a))))
+
+
+@pytest.mark.parametrize("name", ["c3", "c5"])
+def test_feature_fusion_at_full_shape(name):
+    """g = W_fc [low; mid; high] with the 8B (12288 -> 4096) and 70B (24576 -> 8192) matrices, 1 and 7 rows."""
+    E = _E()
+    full = S.get_shape(name)
+    shape = full.with_(n_layers=1, taps=(0, 0, 0))
+    ctx = E.Eagle3Context(shape, max_depth=full.depth, max_topk=full.topk, max_new=8, device=DEV)
+    ctx.set_weights(None, S.draft_weights(full, device=DEV))
+    w_fc = O.as_f64(S.normal(S.SEED, S.TensorIds.D_FC, (full.hidden, 3 * full.hidden), 0.02, 0.0, torch.bfloat16))
+    for M in (1, 7):
+        taps = S.normal(S.SEED + M, S.TensorIds.TAPS, (3, M, full.hidden))
+        ref = O.fuse_features(w_fc, *[O.as_f64(taps[i]) for i in range(3)], rounding="bf16")
+        got = E.eagle3_fuse_features(ctx, *[taps[i].contiguous().to(DEV) for i in range(3)]).cpu().numpy()
+        err = float(np.max(np.abs(got - ref)))
+        print(f"{name} fuse M={M}: max err {err:.5f}, rms err {_rms(got - ref):.5f}, g rms {_rms(ref):.3f}")
+        assert err < TOL
+
+
+def test_c5_draft_online_oracle():
+    """Draft expansion at the 70B shape (FC-free path: 16384-wide draft input, 8192 hidden, 32000 draft ids)."""
+    E = _E()
+    shape = S.get_shape("c5")
+    D, K, N = shape.depth, shape.topk, shape.n_nodes
+    model = PL.OracleModel(shape, cache_layers=False, lazy_embed=True)
+    inp = PL.synthetic_step_inputs(shape)
+    sub = shape.with_(n_layers=1, taps=(0, 0, 0))
+    ctx = E.Eagle3Context(sub, max_depth=D, max_topk=K, max_new=8, device=DEV)
+    T = S.TensorIds
+    tg = {"embed": S.normal(S.SEED, T.EMBED, (shape.vocab, shape.hidden), 0.02, 0.0, torch.bfloat16, DEV),
+          "final_norm": S.normal(S.SEED, T.FINAL_NORM, (shape.hidden,), 0.02, 1.0, torch.bfloat16, DEV)}
+    tg["lm_head"] = tg["embed"]                     # never read by the draft call
+    ctx.set_weights({"layers": [S.layer_weights(sub, 0, device=DEV)], **tg},
+                    S.draft_weights(shape, device=DEV))
+    ks, vs, indptr, plen, P = PL.device_kv([inp["draft_kv"]], 1 + (D - 1) * K, DEV)
+    got = E.eagle3_draft_expand(ctx, inp["g_new"].to(DEV), inp["tok_new"].to(DEV), E.KVCache(ks, vs, indptr, plen, P),
+                                D, K, N, debug=True)
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in got.items()}
+    print("c5 draft: GPU side done, running the oracle", flush=True)
+    tie_tol, level_tol = parity.draft_tolerances(parity.golden("c5"), D)     # from the oracle's stored score drift
+    ref = PL.oracle_draft(shape, model, inp, D, K, N, tol=tie_tol,
+                          follow={"pool_tok": got["pool_tok"], "frontier": got["frontier"], "chosen": got["chosen"]})
+    for key in ("tree_tok", "parent", "depth", "chosen"):
+        assert np.array_equal(got[key], ref[key]), key
+    parity.check_scores("c5", got, ref, level_tol)
+
+
+@pytest.mark.parametrize("order", ["dfs", "mixed"])
+def test_verify_trees_in_other_node_orders(order):
+    """The ABI promises only parent[i] < i.  A 60-node tree renumbered depth-first and in a random parent-first
+    order: the renumbered tree against the oracle, and node for node equal to the level-ordered run."""
+    E = _E()
+    shape = S.get_shape("c2").with_(name="mid", hidden=512, n_heads=8, n_kv_heads=2, intermediate=1024, vocab=4096,
+                                    draft_vocab=2048, n_layers=2, taps=(0, 1, 1), prefix_lo=203, prefix_hi=203)
+    model = PL.OracleModel(shape)
+    N, P = 60, shape.prefix_lo
+    ctx = E.Eagle3Context(shape, max_nodes=64, max_depth=8, max_topk=10, max_new=8, device=DEV)
+    W = PL.device_weights(shape, device=DEV)
+    ctx.set_weights(W["target"], W["draft"])
+    base_parent, _ = S.random_tree(S.SEED, 21, N, 8, 10)
+    parent, old = S.reorder_tree(base_parent, order, seed=S.SEED + 5)
+    depth = O.tree_depth(parent)
+    assert np.any(np.diff(depth) < 0), "the order must not be level order"
+    tok_level = S.uniform_ints(S.SEED, S.TensorIds.TREE_TOK, (N,), 0, shape.vocab).numpy()
+    tok = tok_level[old]
+    pairs = [S.kv_layer(shape, l, P) for l in range(shape.n_layers)]
+    ref = O.tree_verify(shape, model.layer, model.globals(), tok, parent, lambda l: tuple(O.as_f64(t) for t in pairs[l]),
+                        rounding="bf16")
+
+    def run(tk, pr):
+        ks, vs, indptr, plen, _ = PL.device_kv(pairs, N, DEV)
+        lg, tp = E.eagle3_tree_verify(ctx, torch.as_tensor(tk, dtype=torch.int32, device=DEV)[None],
+                                      torch.as_tensor(pr, dtype=torch.int32, device=DEV)[None], E.KVCache(ks, vs, indptr, plen, P))
+        torch.cuda.synchronize()
+        return lg[0].cpu().numpy(), tp[:, 0].cpu().numpy(), [k[P:].float().cpu().numpy() for k in ks]
+
+    lg, tp, kn = run(tok, parent)
+    assert np.max(np.abs(lg - ref["logits"])) < TOL
+    assert np.max(np.abs(tp - ref["taps"])) < TOL
+    for l in range(shape.n_layers):
+        assert np.max(np.abs(kn[l] - ref["k_new"][l])) < TOL
+    lg0, tp0, _ = run(tok_level, base_parent)              # the same tree in level order: node old[i] <-> node i
+    assert np.max(np.abs(lg - lg0[old])) < TOL
+    assert np.max(np.abs(tp - tp0[:, old])) < TOL
+
+
+@pytest.mark.parametrize("n_seq", [48, 64])
+def test_batched_layer_teacher_forced_every_row_and_column(n_seq):
+    """One decoder layer + LM head at the 8B shape over n_seq x 8 = 384 / 512 node rows with ragged caches of
+    512..2048 tokens (the batched-verification launch shapes: every projection takes the many-row GEMM), the same
+    N(0, 8^2) residual rows on both sides, every output element compared."""
+    E = _E()
+    full = S.get_shape("c4")
+    rb = S.ragged_batch(full)
+    B, N = n_seq, full.n_nodes
+    shape = full.with_(n_layers=1, taps=(0, 0, 0), batch=B)
+    layer_id = 5
+    W = S.layer_weights(full, layer_id)
+    tg = S.target_globals(full)
+    ctx = E.Eagle3Context(shape, max_batch=B, max_nodes=N, max_depth=full.depth, max_topk=full.topk, max_new=8, device=DEV)
+    ctx.set_weights({"layers": [{k: v.to(DEV) for k, v in W.items()}], **{k: v.to(DEV) for k, v in tg.items()}}, None)
+    plen = rb["prefix_len"][:B].astype(np.int64)
+    indptr = np.zeros(B + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum(plen + N)
+    total = int(indptr[-1])
+    K_all, V_all = S.kv_layer(full, layer_id, total, device=DEV)
+    kv = E.KVCache([K_all], [V_all], torch.as_tensor(indptr, dtype=torch.int32, device=DEV),
+                   torch.as_tensor(plen, dtype=torch.int32, device=DEV), int(plen.max()))
+    x_in = S.normal(S.SEED + 11, S.TensorIds.TAPS, (B, N, full.hidden), 8.0)
+    tt = torch.as_tensor(rb["tree_tok"][:B], device=DEV)
+    pp = torch.as_tensor(rb["parent"][:B], device=DEV)
+    x_out, logits = E.eagle3_tree_verify_layers(ctx, tt, pp, kv, x_in.to(DEV), 0, 1, want_logits=True)
+    torch.cuda.synchronize()
+    x_out, logits = x_out.cpu().numpy(), logits.cpu().numpy()
+    K_new = K_all.float().cpu().numpy()
+    print(f"{B} x {N} rows: GPU side done, running the oracle per sequence", flush=True)
+    W64, tg64 = O.weights_f64(W), O.weights_f64(tg)
+    worst_x = worst_l = 0.0
+    se_x = se_l = 0.0
+    for b in range(B):
+        P, base = int(plen[b]), int(indptr[b])
+        pair = tuple(O.as_f64(t) for t in S.kv_layer(full, layer_id, P, first_slot=base))
+        ref = O.tree_verify(shape, lambda _l: W64, tg64, rb["tree_tok"][b], rb["parent"][b], lambda _l: pair,
+                            rounding="bf16", x0=O.as_f64(x_in[b]), keep_hidden=True)
+        scale = max(1.0, _rms(ref["hidden"][1]))
+        ex = np.abs(x_out[b] - ref["hidden"][1])
+        el = np.abs(logits[b] - ref["logits"])
+        worst_x, worst_l = max(worst_x, float(ex.max()) / scale), max(worst_l, float(el.max()))
+        se_x += float(np.mean(ex * ex)); se_l += float(np.mean(el * el))
+        assert ex.max() < TOL * scale, f"sequence {b}: residual stream err {ex.max():.4f} (rms {scale:.2f})"
+        assert el.max() < TOL, f"sequence {b}: logits err {el.max():.4f}"
+        assert np.max(np.abs(K_new[base + P:base + P + N] - ref["k_new"][0])) < 4e-2, b     # one bf16 ulp at |k| < 8
+        if b % 16 == 0:
+            print(f"  sequence {b} checked", flush=True)
+    print(f"{B} x {N} rows: stream max err / rms {worst_x:.5f} (rms err {np.sqrt(se_x / B):.5f}), "
+          f"logits max err {worst_l:.5f} (rms err {np.sqrt(se_l / B):.5f})")
+
+
+def test_whole_step_chained_on_the_librarys_own_outputs():
+    """fuse -> draft_expand -> tree_verify -> accept, every stage fed by the previous stage's GPU output (tiny fp32
+    configuration), against the oracle's own chain: tree, accepted length, path and bonus token must be identical."""
+    E = _E()
+    shape = S.get_shape("c1")
+    D, K, N = shape.depth, shape.topk, shape.n_nodes
+    model = PL.OracleModel(shape)
+    inp = PL.real_prefill_inputs(shape, model)
+    ctx = E.Eagle3Context(shape, max_batch=1, max_nodes=N, max_depth=D, max_topk=K, max_new=4, device=DEV)
+    W = PL.device_weights(shape, device=DEV)
+    ctx.set_weights(W["target"], W["draft"])
+    pre = inp["prefill"]
+    # GPU chain
+    taps_last = [torch.from_numpy(pre["taps"][t, -1:, :].copy()).float().to(DEV) for t in range(3)]
+    g = E.eagle3_fuse_features(ctx, *taps_last)
+    ks, vs, indptr, plen, P = PL.device_kv([inp["draft_kv"]], 1 + (D - 1) * K, DEV)
+    tree = E.eagle3_draft_expand(ctx, g, inp["tok_new"].to(DEV), E.KVCache(ks, vs, indptr, plen, P), D, K, N, debug=True)
+    tt, pp = tree["tree_tok"][None].contiguous(), tree["parent"][None].contiguous()
+    ks, vs, indptr, plen, P = PL.device_kv(inp["target_kv"], N, DEV)
+    logits, taps = E.eagle3_tree_verify(ctx, tt, pp, E.KVCache(ks, vs, indptr, plen, P))
+    U = S.uniform01(S.SEED + 6, S.TensorIds.UNIFORMS, (1, 2 * N)).to(DEV)
+    al0, path0, bonus0 = E.eagle3_accept(ctx, logits, tt, pp, 0.0)
+    al1, path1, bonus1 = E.eagle3_accept(ctx, logits, tt, pp, 1.0, U)
+    torch.cuda.synchronize()
+    # oracle chain
+    g_ref = O.fuse_features(model.draft()["w_fc"], *[pre["taps"][t, -1:, :] for t in range(3)])
+    inp_ref = dict(inp, g_new=torch.from_numpy(g_ref))
+    got = {k: v.cpu().numpy() for k, v in tree.items()}
+    ref = PL.oracle_draft(shape, model, inp_ref, D, K, N, tol=1e-4,
+                          follow={"pool_tok": got["pool_tok"], "frontier": got["frontier"], "chosen": got["chosen"]})
+    assert ref["n_followed"] == 0 or ref["min_gap"] <= 1e-4
+    for key in ("tree_tok", "parent", "depth"):
+        assert np.array_equal(got[key], ref[key]), key
+    vref = PL.oracle_verify(shape, model, inp, ref["tree_tok"], ref["parent"])
+    assert np.max(np.abs(logits[0].cpu().numpy() - vref["logits"])) < 1e-4
+    assert np.max(np.abs(taps[:, 0].cpu().numpy() - vref["taps"])) < 1e-4
+    n_acc, rpath, rbonus = O.accept_greedy(vref["logits"], ref["tree_tok"], ref["parent"])
+    srt = np.sort(vref["logits"][rpath], axis=1)
+    assert (srt[:, -1] - srt[:, -2]).min() > 1e-3, "the seeded case must have clear arg-max margins on the walk"
+    assert (int(al0[0]), int(bonus0[0])) == (n_acc, rbonus)
+    assert path0[0].cpu().numpy().tolist() == rpath + [-1] * (N - len(rpath))
+    n_acc, rpath, rbonus, margin = O.accept_stochastic(vref["logits"], ref["tree_tok"], ref["parent"], 1.0,
+                                                        U[0].double().cpu().numpy())
+    assert margin > 1e-4, "the seeded uniforms must not sit on a decision threshold"
+    assert (int(al1[0]), int(bonus1[0])) == (n_acc, rbonus)
+    assert path1[0].cpu().numpy().tolist() == rpath + [-1] * (N - len(rpath))

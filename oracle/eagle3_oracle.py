@@ -486,6 +486,82 @@ def bonus_admissible(info, bonus, eps):
     return lo - eps <= target <= cdf[bonus] + eps
 
 
+# ----------------------------------------------------------------------------- across steps
+
+def commit_path(tree_tok, path, bonus, taps, k_new, v_new):
+    """What one step hands to the next (Section 2.1: the accepted draft tokens are kept, everything after the first
+    rejection is discarded; Section 3.1: the features recorded during this verification feed the next draft).
+    path = accepted node ids from the root (accept_len + 1 of them).  Returns
+      k_keep, v_keep [L, n, Hkv, d]  cache rows of the accepted nodes, in path order (they extend the prefix)
+      taps_new [3, n, k]             low / mid / high features of the accepted positions
+      tok_new [n]                    the token FOLLOWING each accepted position: the next node on the path, and the
+                                     bonus token after the last one (the next step's root)
+    with n = accept_len + 1."""
+    path = np.asarray(path, dtype=np.int64)
+    tok_new = np.concatenate([np.asarray(tree_tok, dtype=np.int64)[path[1:]], [int(bonus)]])
+    return k_new[:, path], v_new[:, path], taps[:, path], tok_new
+
+
+def greedy_decode(shape, get_layer, tg, prompt, n_tokens):
+    """Ordinary autoregressive arg-max decoding of the target (Appendix A "Vanilla"), the reference that greedy
+    speculative decoding must reproduce token for token.  Plain and slow: one full causal forward per token."""
+    toks = [int(t) for t in prompt]
+    for _ in range(n_tokens):
+        out = prefill(shape, get_layer, tg, np.asarray(toks))
+        toks.append(int(np.argmax(out["logits"][-1])))
+    return toks[len(prompt):]
+
+
+def speculative_decode(shape, get_layer, tg, dw, prompt, n_steps, depth, topk, n_nodes, temperature=0.0,
+                       uniforms=None, tree_hook=None, rounding="none"):
+    """The whole pipeline of Section 3.1 over several draft-verify cycles, one sequence.
+
+    Prefill: target forward over the prompt (its taps are the features g of every prompt position, its last arg-max
+    is the first root), draft cache = the draft layer's keys/values over (g_i, token_{i+1}).  Each cycle: draft tree
+    from the features of the positions accepted last cycle, tree verification, acceptance walk, commit.
+    tree_hook(step, tree_tok, parent, depth) -> tree_tok lets a test replace drafted tokens (the tree's SHAPE stays the
+    draft's).  Returns dict(tokens = everything emitted after the prompt, accept_lens, trees, per-step records)."""
+    rd = _rounder(rounding)
+    embed = tg["embed"]
+    prompt = np.asarray(prompt, dtype=np.int64)
+    P = len(prompt)
+    pre = prefill(shape, get_layer, tg, prompt, rounding=rounding)
+    K_t = [pre["k_new"][l] for l in range(shape.n_layers)]          # target cache per layer [P, Hkv, d]
+    V_t = [pre["v_new"][l] for l in range(shape.n_layers)]
+    g_all = fuse_features(dw["w_fc"], pre["taps"][0], pre["taps"][1], pre["taps"][2], rounding=rounding)
+    cap = P + n_steps * (depth + 1) + (depth - 1) * topk + 8
+    Kd = np.zeros((cap, shape.n_kv_heads, shape.head_dim))
+    Vd = np.zeros_like(Kd)
+    if P > 1:                                                        # draft rows (g_i, token_{i+1}), i < P-1
+        draft_forward(shape, dw, embed, g_all[:P - 1], prompt[1:], np.arange(P - 1), Kd, Vd, 0, 0,
+                      np.tril(np.ones((P - 1, P - 1), dtype=bool)), rd)
+    n_d = P - 1                                                      # valid draft cache entries
+    root = int(np.argmax(pre["logits"][-1])) if temperature == 0 else None
+    assert root is not None, "the first token is taken greedily by the caller; pass temperature 0 or extend here"
+    g_new, tok_new = g_all[P - 1:P], np.array([root], dtype=np.int64)
+    emitted, accept_lens, records = [root], [], []
+    for step in range(n_steps):
+        tree = draft_expand(shape, dw, embed, g_new, tok_new, Kd, Vd, n_d, depth, topk, n_nodes, rounding=rounding)
+        n_d += len(tok_new)                                          # forward 1's rows stay in the draft cache
+        tree_tok = tree["tree_tok"] if tree_hook is None else np.asarray(
+            tree_hook(step, tree["tree_tok"].copy(), tree["parent"], tree["depth"], emitted))
+        ver = tree_verify(shape, get_layer, tg, tree_tok, tree["parent"], lambda l: (K_t[l], V_t[l]), rounding=rounding)
+        if temperature == 0:
+            n_acc, path, bonus = accept_greedy(ver["logits"], tree_tok, tree["parent"])
+        else:
+            n_acc, path, bonus, _ = accept_stochastic(ver["logits"], tree_tok, tree["parent"], temperature, uniforms[step])
+        k_keep, v_keep, taps_new, tok_new = commit_path(tree_tok, path, bonus, ver["taps"], ver["k_new"], ver["v_new"])
+        for l in range(shape.n_layers):
+            K_t[l] = np.concatenate([K_t[l], k_keep[l]], axis=0)
+            V_t[l] = np.concatenate([V_t[l], v_keep[l]], axis=0)
+        g_new = fuse_features(dw["w_fc"], taps_new[0], taps_new[1], taps_new[2], rounding=rounding)
+        emitted += [int(t) for t in tok_new]
+        accept_lens.append(n_acc)
+        records.append({"tree_tok": tree_tok, "parent": tree["parent"], "path": path, "bonus": bonus, "tok_new": tok_new})
+    return {"tokens": emitted, "accept_lens": accept_lens, "records": records,
+            "tau": float(np.mean(np.asarray(accept_lens) + 1.0))}
+
+
 # ----------------------------------------------------------------------------- plumbing for whole-step use
 
 def weights_f64(d):

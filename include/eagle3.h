@@ -190,6 +190,27 @@ int eagle3_accept(eagle3_ctx* ctx, int32_t B, int32_t N, const float* logits, co
                   const int32_t* parent, float temperature, const float* uniforms,
                   int32_t* accept_len, int32_t* path, int32_t* bonus_tok, eagle3_stream stream);
 
+/* Between two steps.  Section 2.1: the accepted draft tokens are kept and everything after the first rejection is
+ * discarded; Section 3.1: the features recorded during this verification are the next draft's input.  For every
+ * sequence b with path[b][0..a] (a = accept_len[b]) the call
+ *   - moves, in every target layer and in place, the cache rows of the accepted nodes from slots
+ *     prefix_len[b] + path[b][j] to slots prefix_len[b] + j (keys and values);
+ *   - writes taps_new[t][b][j] = taps[t][b][path[b][j]] (j <= a): the low / mid / high features of the accepted
+ *     positions, ready for eagle3_fuse_features;
+ *   - writes tok_new[b][j] = the token FOLLOWING accepted position j: tree_tok[b][path[b][j+1]] for j < a and
+ *     bonus_tok[b] for j = a (the next tree's root), and n_new[b] = a + 1;
+ *   - adds a + 1 to prefix_len[b] and, if draft_prefix_len is given, draft_rows to draft_prefix_len[b] (the rows that
+ *     this step's draft forward 1 appended to the draft cache stay valid whatever was accepted).
+ *   tree_tok, path [B, N]; accept_len, bonus_tok [B] (as written by eagle3_accept); kv: the target cache of the
+ *   verification (kv->prefix_len is NOT used: prefix_len, DEVICE [B], is read and then updated; it may be the same
+ *   array); taps [3, B, N, hidden] from eagle3_tree_verify; rows: row capacity of the outputs per sequence
+ *   (a + 1 is clamped to it); taps_new fp32 [3, B, rows, hidden] or NULL; tok_new int32 [B, rows]; n_new int32 [B].
+ * The caller keeps kv->max_prefix_len (a host bound) ahead of the device lengths, e.g. by adding rows per step. */
+int eagle3_commit(eagle3_ctx* ctx, int32_t B, int32_t N, const int32_t* tree_tok, const int32_t* path,
+                  const int32_t* accept_len, const int32_t* bonus_tok, const eagle3_kv* kv, int32_t* prefix_len,
+                  const float* taps, int32_t rows, float* taps_new, int32_t* tok_new, int32_t* n_new,
+                  int32_t* draft_prefix_len, int32_t draft_rows, eagle3_stream stream);
+
 /* For callers that cannot allocate device memory and hold no context: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  The same acceptance walk as eagle3_accept (same kernels, same
  * results) with its per-(row, 2048-logit chunk) statistics kept in a fixed 1 MiB device array inside the library

@@ -17,7 +17,7 @@ EAGLE3_FP32, EAGLE3_BF16 = 0, 1
 EXPORTS = ["eagle3_create", "eagle3_destroy", "eagle3_workspace_bytes", "eagle3_set_workspace", "eagle3_set_weights",
            "eagle3_strerror", "eagle3_last_error", "eagle3_profile_begin", "eagle3_profile_read", "eagle3_profile_end",
            "eagle3_fuse_features", "eagle3_draft_expand",
-           "eagle3_tree_verify", "eagle3_tree_verify_layers", "eagle3_accept", "eagle3_accept_static"]
+           "eagle3_tree_verify", "eagle3_tree_verify_layers", "eagle3_accept", "eagle3_accept_static", "eagle3_commit"]
 
 
 class Config(C.Structure):
@@ -85,6 +85,9 @@ def lib():
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.eagle3_accept_static.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float,
                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.eagle3_commit.argtypes = [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 4 + [C.POINTER(KV), C.c_void_p,
+                                    C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                    C.c_void_p]
         _lib = L
     return _lib
 
@@ -133,11 +136,19 @@ class KVCache:
     def __init__(self, k_layers, v_layers, kv_indptr, prefix_len, max_prefix_len):
         self.k_layers, self.v_layers = list(k_layers), list(v_layers)
         self.kv_indptr, self.prefix_len, self.max_prefix_len = kv_indptr, prefix_len, int(max_prefix_len)
+        self._build()
+
+    def set_max_prefix_len(self, n):
+        """The host-side bound on prefix_len (sizes launches); to be kept ahead of the device values."""
+        self.max_prefix_len = int(n)
+        self.c.max_prefix_len = int(n)
+
+    def _build(self):
         n = len(self.k_layers)
         self._k = (C.c_void_p * n)(*[_ptr(t) for t in self.k_layers])
         self._v = (C.c_void_p * n)(*[_ptr(t) for t in self.v_layers])
         self.c = KV(C.cast(self._k, C.POINTER(C.c_void_p)), C.cast(self._v, C.POINTER(C.c_void_p)),
-                    _ptr(kv_indptr, torch.int32), _ptr(prefix_len, torch.int32), self.max_prefix_len)
+                    _ptr(self.kv_indptr, torch.int32), _ptr(self.prefix_len, torch.int32), self.max_prefix_len)
 
 
 class Eagle3Context:
@@ -298,3 +309,20 @@ def eagle3_accept_static(logits, tree_tok, parent, temperature=0.0, uniforms=Non
                                       _ptr(uniforms, torch.float32) if uniforms is not None else None, _ptr(accept_len),
                                       _ptr(path), _ptr(bonus), _stream()))
     return accept_len, path, bonus
+
+
+def eagle3_commit(ctx, tree_tok, path, accept_len, bonus, kv, taps, rows, draft_kv=None, draft_rows=0):
+    """Commits the accepted paths: cache rows compacted in place, kv.prefix_len advanced (and draft_kv.prefix_len by
+    draft_rows).  Returns (taps_new [3,B,rows,k], tok_new [B,rows], n_new [B])."""
+    B, N = tree_tok.shape
+    dev = tree_tok.device
+    taps_new = torch.zeros(3, B, rows, ctx.cfg.hidden, dtype=torch.float32, device=dev)
+    tok_new = torch.zeros(B, rows, dtype=torch.int32, device=dev)
+    n_new = torch.zeros(B, dtype=torch.int32, device=dev)
+    _check(lib().eagle3_commit(ctx._h, B, N, _ptr(tree_tok, torch.int32), _ptr(path, torch.int32),
+                               _ptr(accept_len, torch.int32), _ptr(bonus, torch.int32), C.byref(kv.c),
+                               _ptr(kv.prefix_len, torch.int32), _ptr(taps, torch.float32), int(rows), _ptr(taps_new),
+                               _ptr(tok_new), _ptr(n_new),
+                               _ptr(draft_kv.prefix_len, torch.int32) if draft_kv is not None else None, int(draft_rows),
+                               _stream()))
+    return taps_new, tok_new, n_new

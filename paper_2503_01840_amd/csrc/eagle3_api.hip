@@ -494,4 +494,21 @@ int eagle3_accept(eagle3_ctx* ctx, int32_t B, int32_t N, const float* logits, co
   return EAGLE3_OK;
 }
 
+int eagle3_commit(eagle3_ctx* ctx, int32_t B, int32_t N, const int32_t* tree_tok, const int32_t* path,
+                  const int32_t* accept_len, const int32_t* bonus_tok, const eagle3_kv* kv, int32_t* prefix_len,
+                  const float* taps, int32_t rows, float* taps_new, int32_t* tok_new, int32_t* n_new,
+                  int32_t* draft_prefix_len, int32_t draft_rows, eagle3_stream stream) {
+  if (!ctx || !tree_tok || !path || !accept_len || !bonus_tok || !kv || !prefix_len || !taps || !tok_new || !n_new)
+    return EAGLE3_E_NULL;
+  if (!kv->k || !kv->v || !kv->kv_indptr) return EAGLE3_E_NULL;
+  const eagle3_config& c = ctx->cfg;
+  if (B < 1 || B > c.max_batch || N < 1 || N > c.max_nodes || rows < 1 || draft_rows < 0) return EAGLE3_E_SHAPE;
+  for (int l = 0; l < c.n_layers; ++l)
+    if (!kv->k[l] || !kv->v[l]) return EAGLE3_E_NULL;
+  CK(launch_commit(kv->k, kv->v, c.n_layers, kv->kv_indptr, prefix_len, tree_tok, path, accept_len, bonus_tok, taps, B, N,
+                   c.hidden, (int)(c.n_kv_heads * c.head_dim * ctx->act_size), rows, taps_new, tok_new, n_new,
+                   draft_prefix_len, draft_rows, (hipStream_t)stream));
+  return EAGLE3_OK;
+}
+
 }  // extern "C"

@@ -120,3 +120,12 @@ size_t accept_scratch_floats(int R, int V);
 hipError_t launch_accept(const float* logits, const int32_t* tree_tok, const int32_t* parent, int B, int N, int V,
                          float temperature, const float* uniforms, float* scratch, int32_t* accept_len, int32_t* path,
                          int32_t* bonus, hipStream_t st);
+
+// ---------------------------------------------------------------- commit (commit.hip)
+// Moves the accepted nodes' cache rows to the front of the tree slots (every layer, in place), gathers their
+// features and following tokens, advances the prefix lengths.  k_layers / v_layers: host arrays of device pointers.
+hipError_t launch_commit(void* const* k_layers, void* const* v_layers, int n_layers, const int32_t* kv_indptr,
+                         int32_t* prefix_len, const int32_t* tree_tok, const int32_t* path, const int32_t* accept_len,
+                         const int32_t* bonus, const float* taps, int B, int N, int hidden, int row_bytes, int rows,
+                         float* taps_new, int32_t* tok_new, int32_t* n_new, int32_t* draft_prefix_len, int draft_rows,
+                         hipStream_t st);

@@ -1,0 +1,145 @@
+"""Several draft-verify cycles on the GPU, each fed by the previous one through eagle3_commit: the emitted tokens
+must be the target's plain greedy decoding (Section 2.1: lossless), and the per-cycle accepted lengths give tau
+(Section 4 "Metrics") mechanically."""
+import numpy as np
+import pytest
+import torch
+
+import eagle3_synth as S
+from oracle import eagle3_oracle as O
+import pipeline as PL
+from test_oracle_decode import planted_hook
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def gpu_decode(E, ctx, shape, state, n_steps, D, K, N, hook=None):
+    """state: dict(kv, dkv, g_new [n,k] device, tok_new [n] device, P (target prefix), Pd (draft prefix)).
+    Returns (emitted tokens after the first root, accept_lens, per-step trees)."""
+    kv, dkv = state["kv"], state["dkv"]
+    g_new, tok_new = state["g_new"], state["tok_new"]
+    P, Pd = state["P"], state["Pd"]
+    emitted, accept_lens, trees = [int(tok_new[-1])], [], []
+    for step in range(n_steps):
+        n_prev = g_new.shape[0]
+        tree = E.eagle3_draft_expand(ctx, g_new, tok_new, dkv, D, K, N)
+        tt, pp = tree["tree_tok"][None].contiguous(), tree["parent"][None].contiguous()
+        if hook is not None:
+            new_tok = hook(step, tt[0].cpu().numpy().copy(), pp[0].cpu().numpy(), tree["depth"].cpu().numpy(), emitted)
+            tt = torch.as_tensor(new_tok, dtype=torch.int32, device=DEV)[None].contiguous()
+        logits, taps = E.eagle3_tree_verify(ctx, tt, pp, kv)
+        al, path, bonus = E.eagle3_accept(ctx, logits, tt, pp, 0.0)
+        taps_new, tok_rows, n_new = E.eagle3_commit(ctx, tt, path, al, bonus, kv, taps, D + 1, draft_kv=dkv, draft_rows=n_prev)
+        n = int(n_new[0])                                            # the host needs the tokens anyway
+        assert n == int(al[0]) + 1
+        P, Pd = P + n, Pd + n_prev
+        assert int(kv.prefix_len[0]) == P and int(dkv.prefix_len[0]) == Pd
+        kv.set_max_prefix_len(P)
+        dkv.set_max_prefix_len(Pd)
+        g_new = E.eagle3_fuse_features(ctx, *[taps_new[t, 0, :n].contiguous() for t in range(3)])
+        tok_new = tok_rows[0, :n].contiguous()
+        emitted += tok_new.cpu().numpy().tolist()
+        accept_lens.append(n - 1)
+        trees.append((tt[0].cpu().numpy(), pp[0].cpu().numpy(), path[0].cpu().numpy()))
+    return emitted, accept_lens, trees
+
+
+def oracle_prefill_state(E, shape, model, prompt, extra_slots):
+    """Caches, features and the first root from the ORACLE's prefill, mirrored onto the device."""
+    P = len(prompt)
+    pre = O.prefill(shape, model.layer, model.globals(), prompt)
+    dw, emb = model.draft(), model.globals()["embed"]
+    g_all = O.fuse_features(dw["w_fc"], pre["taps"][0], pre["taps"][1], pre["taps"][2])
+    Kd = np.zeros((P - 1, shape.n_kv_heads, shape.head_dim)); Vd = np.zeros_like(Kd)
+    O.draft_forward(shape, dw, emb, g_all[:P - 1], prompt[1:], np.arange(P - 1), Kd, Vd, 0, 0,
+                    np.tril(np.ones((P - 1, P - 1), dtype=bool)), lambda a: a)
+    pairs = [(torch.from_numpy(pre["k_new"][l]).float(), torch.from_numpy(pre["v_new"][l]).float()) for l in range(shape.n_layers)]
+    ks, vs, indptr, plen, _ = PL.device_kv(pairs, extra_slots, DEV)
+    dks, dvs, dindptr, dplen, _ = PL.device_kv([(torch.from_numpy(Kd).float(), torch.from_numpy(Vd).float())], extra_slots, DEV)
+    root = int(np.argmax(pre["logits"][-1]))
+    return {"kv": E.KVCache(ks, vs, indptr, plen, P), "dkv": E.KVCache(dks, dvs, dindptr, dplen, P - 1),
+            "g_new": torch.from_numpy(g_all[P - 1:P].copy()).float().to(DEV),
+            "tok_new": torch.tensor([root], dtype=torch.int32, device=DEV), "P": P, "Pd": P - 1}
+
+
+def test_multi_step_greedy_decode_equals_plain_greedy_decoding():
+    import paper_2503_01840_amd as E
+    shape = S.get_shape("c1")
+    D, K, N = shape.depth, shape.topk, 30
+    model = PL.OracleModel(shape)
+    prompt = S.uniform_ints(S.SEED, S.TensorIds.PREFIX_TOK, (12,), 0, shape.vocab).numpy()
+    ref = O.greedy_decode(shape, model.layer, model.globals(), prompt, 48)
+    ctx = E.Eagle3Context(shape, max_batch=1, max_nodes=32, max_depth=D, max_topk=K, max_new=D + 1, device=DEV)
+    W = PL.device_weights(shape, device=DEV)
+    ctx.set_weights(W["target"], W["draft"])
+    wanted = [3, 0, 1, 2, 3, 1, 2, 3, 0, 3, 2, 1]
+    n_steps = 14
+    hook = planted_hook(ref, wanted)
+    state = oracle_prefill_state(E, shape, model, prompt, n_steps * (D + 1) + N + (D - 1) * K + 8)
+    emitted, accept_lens, trees = gpu_decode(E, ctx, shape, state, n_steps, D, K, N, hook)
+    assert len(emitted) >= 32
+    assert emitted == ref[:len(emitted)], "greedy speculative decoding must reproduce plain greedy decoding"
+    want = (wanted * 2)[:n_steps]
+    assert all(a >= w for a, w in zip(accept_lens, want))
+    assert max(accept_lens) == D and min(accept_lens) == 0          # every compaction distance occurs
+    # the oracle's own multi-step run with the same planted continuations: same accepted lengths, same paths
+    out = O.speculative_decode(shape, model.layer, model.globals(), model.draft(), prompt, n_steps, D, K, N, tree_hook=hook)
+    assert out["tokens"] == emitted
+    assert out["accept_lens"] == accept_lens
+    for rec, (tt, pp, path) in zip(out["records"], trees):
+        assert np.array_equal(rec["parent"], pp) and np.array_equal(rec["tree_tok"], tt)
+        assert path[:len(rec["path"])].tolist() == list(rec["path"])
+    tau = float(np.mean(np.asarray(accept_lens) + 1))
+    print(f"{len(emitted)} tokens in {n_steps} cycles: tau = {tau:.2f} (planted), accepted lengths {accept_lens}")
+    # without planted tokens the random-weight draft almost never guesses right: still lossless
+    state = oracle_prefill_state(E, shape, model, prompt, n_steps * (D + 1) + N + (D - 1) * K + 8)
+    emitted2, accept2, _ = gpu_decode(E, ctx, shape, state, 6, D, K, N, None)
+    assert emitted2 == ref[:len(emitted2)]
+
+
+def test_commit_moves_rows_in_every_layer_for_a_ragged_batch():
+    """bf16 storage, 3 sequences with different prefixes and paths (including a path whose sources and destinations
+    overlap: 0, 2, 5, 6, 9 ... and the longest possible chain), every layer's keys and values checked."""
+    import paper_2503_01840_amd as E
+    shape = S.get_shape("c2").with_(name="small", hidden=256, n_heads=4, n_kv_heads=2, intermediate=512, vocab=1024,
+                                    draft_vocab=512, n_layers=3, taps=(0, 1, 2))
+    B, N = 3, 24
+    ctx = E.Eagle3Context(shape, max_batch=B, max_nodes=N, max_depth=8, max_topk=4, max_new=8, device=DEV)
+    plens = np.array([5, 0, 130])
+    indptr = np.zeros(B + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum(plens + N + 2)
+    total = int(indptr[-1])
+    ks, vs = zip(*[tuple(t.to(DEV) for t in S.kv_layer(shape, l, total)) for l in range(shape.n_layers)])
+    k0 = [k.clone() for k in ks]; v0 = [v.clone() for v in vs]
+    plen_d = torch.as_tensor(plens, dtype=torch.int32, device=DEV)
+    kv = E.KVCache(ks, vs, torch.as_tensor(indptr, dtype=torch.int32, device=DEV), plen_d, int(plens.max()))
+    paths = [[0, 2, 5, 6, 9, 10, 17, 20, 23], [0], list(range(0, 24))[:12]]
+    paths[2] = [0, 1, 2, 3, 5, 6, 7, 8, 10, 12, 13, 23]
+    path = np.full((B, N), -1, dtype=np.int32)
+    for b, p in enumerate(paths):
+        path[b, :len(p)] = p
+    al = torch.tensor([len(p) - 1 for p in paths], dtype=torch.int32, device=DEV)
+    tok = S.uniform_ints(S.SEED, S.TensorIds.TREE_TOK, (B, N), 0, shape.vocab).to(DEV)
+    bonus = torch.tensor([7, 8, 9], dtype=torch.int32, device=DEV)
+    taps = S.normal(S.SEED, S.TensorIds.TAPS, (3, B, N, shape.hidden)).to(DEV)
+    rows = 12
+    dpl = torch.tensor([4, 4, 4], dtype=torch.int32, device=DEV)
+
+    class _D:                                   # only the draft prefix lengths are touched
+        prefix_len = dpl
+    taps_new, tok_new, n_new = E.eagle3_commit(ctx, tok, torch.as_tensor(path, device=DEV), al, bonus, kv, taps, rows,
+                                               draft_kv=_D, draft_rows=3)
+    torch.cuda.synchronize()
+    assert n_new.cpu().tolist() == [len(p) for p in paths]
+    assert plen_d.cpu().tolist() == (plens + np.array([len(p) for p in paths])).tolist()
+    assert dpl.cpu().tolist() == [7, 7, 7]
+    for b, p in enumerate(paths):
+        first = int(indptr[b] + plens[b])
+        want_tok = [int(tok[b, q]) for q in p[1:]] + [int(bonus[b])]
+        assert tok_new[b, :len(p)].cpu().tolist() == want_tok
+        assert torch.equal(taps_new[:, b, :len(p)], taps[:, b, p])
+        for l in range(shape.n_layers):
+            for cur, old in ((ks[l], k0[l]), (vs[l], v0[l])):
+                assert torch.equal(cur[first:first + len(p)], old[first + torch.as_tensor(p, device=DEV)]), (b, l)
+                assert torch.equal(cur[int(indptr[b]):first], old[int(indptr[b]):first])   # the context did not move

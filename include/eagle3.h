@@ -190,6 +190,24 @@ int eagle3_accept(eagle3_ctx* ctx, int32_t B, int32_t N, const float* logits, co
                   const int32_t* parent, float temperature, const float* uniforms,
                   int32_t* accept_len, int32_t* path, int32_t* bonus_tok, eagle3_stream stream);
 
+/* Section 3.1, first paragraph of the pipeline: during the prefill phase the target model runs over the prompt, the
+ * low / mid / high feature sequences of its positions are recorded and fused, and the draft model's context is built
+ * from them.  One sequence.  The T prompt tokens are run through every target layer in chunks of
+ * min(max_nodes, max_new) positions (each chunk a chain on top of everything cached before it), their keys and
+ * values are appended to the target cache at slots prefix_len .. prefix_len + T - 1, and for every position i whose
+ * following token is known (all but the last) the draft layer's key / value of the row (g_i, tokens[i+1]) is appended
+ * to the draft cache (a draft row's key and value depend only on that row, so no draft attention runs here).
+ *   tokens       DEVICE int32 [T]
+ *   kv, draft_kv  target cache (all layers) and draft cache (one layer), one sequence each; BOTH prefix_len arrays
+ *                 are read and then ADVANCED by the call (by T and by T - 1); max_prefix_len bounds the values on
+ *                 entry; the caches need T (T - 1) free slots after their prefixes
+ *   g_last       fp32 [hidden]  fused feature of the last prompt position: with the first sampled token it is the
+ *                               n_new = 1 input of the first eagle3_draft_expand
+ *   logits_last  fp32 [vocab]   next-token logits after the prompt
+ * Requires T >= 1 and both weight sets. */
+int eagle3_prefill(eagle3_ctx* ctx, const int32_t* tokens, int32_t T, const eagle3_kv* kv, const eagle3_kv* draft_kv,
+                   float* g_last, float* logits_last, eagle3_stream stream);
+
 /* Between two steps.  Section 2.1: the accepted draft tokens are kept and everything after the first rejection is
  * discarded; Section 3.1: the features recorded during this verification are the next draft's input.  For every
  * sequence b with path[b][0..a] (a = accept_len[b]) the call

@@ -17,7 +17,7 @@ EAGLE3_FP32, EAGLE3_BF16 = 0, 1
 EXPORTS = ["eagle3_create", "eagle3_destroy", "eagle3_workspace_bytes", "eagle3_set_workspace", "eagle3_set_weights",
            "eagle3_strerror", "eagle3_last_error", "eagle3_profile_begin", "eagle3_profile_read", "eagle3_profile_end",
            "eagle3_fuse_features", "eagle3_draft_expand",
-           "eagle3_tree_verify", "eagle3_tree_verify_layers", "eagle3_accept", "eagle3_accept_static", "eagle3_commit"]
+           "eagle3_tree_verify", "eagle3_tree_verify_layers", "eagle3_accept", "eagle3_accept_static", "eagle3_commit", "eagle3_prefill"]
 
 
 class Config(C.Structure):
@@ -88,6 +88,8 @@ def lib():
         L.eagle3_commit.argtypes = [C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 4 + [C.POINTER(KV), C.c_void_p,
                                     C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                     C.c_void_p]
+        L.eagle3_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(KV), C.POINTER(KV), C.c_void_p, C.c_void_p,
+                                     C.c_void_p]
         _lib = L
     return _lib
 
@@ -326,3 +328,16 @@ def eagle3_commit(ctx, tree_tok, path, accept_len, bonus, kv, taps, rows, draft_
                                _ptr(draft_kv.prefix_len, torch.int32) if draft_kv is not None else None, int(draft_rows),
                                _stream()))
     return taps_new, tok_new, n_new
+
+
+def eagle3_prefill(ctx, tokens, kv, draft_kv):
+    """Runs the prompt through the target (cache, features) and builds the draft cache; advances both prefix_len
+    arrays on the device and the host bounds.  Returns (g_last [hidden], logits_last [vocab])."""
+    T = tokens.shape[0]
+    g_last = torch.empty(ctx.cfg.hidden, dtype=torch.float32, device=tokens.device)
+    logits = torch.empty(ctx.cfg.vocab, dtype=torch.float32, device=tokens.device)
+    _check(lib().eagle3_prefill(ctx._h, _ptr(tokens, torch.int32), T, C.byref(kv.c), C.byref(draft_kv.c), _ptr(g_last),
+                                _ptr(logits), _stream()))
+    kv.set_max_prefix_len(kv.max_prefix_len + T)
+    draft_kv.set_max_prefix_len(draft_kv.max_prefix_len + T - 1)
+    return g_last, logits

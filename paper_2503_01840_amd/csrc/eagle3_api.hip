@@ -66,6 +66,8 @@ struct eagle3_ctx {
   int32_t* depth; uint32_t* mask; int32_t* slot; float* cs; SeqInfo* seq;
   float* accept_stats;
   float* z; float* a_buf; int32_t* pos1; float* topk_scratch; DraftState ds;
+  int chunk_max;                        // rows per prefill chunk
+  int32_t* chain_parent; float* chunk_taps; float* chunk_g;
 
   void carve(void* base) {
     const eagle3_config& c = cfg;
@@ -103,6 +105,9 @@ struct eagle3_ctx {
     ds.row_slot = cv.take<int32_t>(c.max_topk);
     ds.row_mask = cv.take<uint32_t>((size_t)c.max_topk * 4);
     ds.seq = cv.take<SeqInfo>(1);
+    chain_parent = cv.take<int32_t>(64);
+    chunk_taps = cv.take<float>((size_t)3 * chunk_max * k);
+    chunk_g = cv.take<float>((size_t)chunk_max * k);
     ws_need = cv.off;
   }
 
@@ -194,6 +199,7 @@ int eagle3_create(const eagle3_config* cfg, eagle3_ctx** out) {
   ctx->Md_max = std::max(c.max_new, c.max_topk);
   ctx->Rall = std::max(ctx->R_max, ctx->Md_max);
   ctx->a_rows = c.max_new + (c.max_depth - 1) * c.max_topk;
+  ctx->chunk_max = std::min(c.max_nodes, c.max_new);
   ctx->pool_max = 1 + c.max_topk + (c.max_depth - 1) * c.max_topk * c.max_topk;
   const size_t widest = std::max<size_t>({(size_t)(c.n_heads + 2 * c.n_kv_heads) * c.head_dim, (size_t)c.hidden,
                                           ctx->bf16 ? (size_t)0 : (size_t)2 * c.intermediate});
@@ -299,12 +305,19 @@ int eagle3_profile_end(eagle3_ctx* ctx) {
   return EAGLE3_OK;
 }
 
+static int fuse_rows(eagle3_ctx* ctx, const float* low, const float* mid, const float* high, int M, float* g_out,
+                     hipStream_t st);
+
 int eagle3_fuse_features(eagle3_ctx* ctx, const float* low, const float* mid, const float* high, int32_t M,
                          float* g_out, eagle3_stream stream) {
   if (!ctx || !low || !mid || !high || !g_out) return EAGLE3_E_NULL;
   if (!ctx->ws || !ctx->has_draft) return EAGLE3_E_STATE;
   if (M < 1 || M > ctx->cfg.max_new) return EAGLE3_E_SHAPE;
-  hipStream_t st = (hipStream_t)stream;
+  return fuse_rows(ctx, low, mid, high, M, g_out, (hipStream_t)stream);
+}
+
+static int fuse_rows(eagle3_ctx* ctx, const float* low, const float* mid, const float* high, int M, float* g_out,
+                     hipStream_t st) {
   const int k = ctx->cfg.hidden;
   CK(launch_pack3(ctx->bf16, low, mid, high, M, k, ctx->act_k, st));
   GemmWeights W = {{ctx->dw.w_fc, nullptr, nullptr}, {k, 0, 0}, 1, 0};
@@ -491,6 +504,57 @@ int eagle3_accept(eagle3_ctx* ctx, int32_t B, int32_t N, const float* logits, co
   if (B < 1 || B > ctx->cfg.max_batch || N < 1 || N > ctx->cfg.max_nodes || !(temperature >= 0.f)) return EAGLE3_E_SHAPE;
   CK(launch_accept(logits, tree_tok, parent, B, N, ctx->cfg.vocab, temperature, uniforms, ctx->accept_stats, accept_len,
                    path, bonus_tok, (hipStream_t)stream));
+  return EAGLE3_OK;
+}
+
+int eagle3_prefill(eagle3_ctx* ctx, const int32_t* tokens, int32_t T, const eagle3_kv* kv, const eagle3_kv* dkv,
+                   float* g_last, float* logits_last, eagle3_stream stream) {
+  if (!ctx || !tokens || !kv || !dkv || !g_last || !logits_last) return EAGLE3_E_NULL;
+  if (!kv->k || !kv->v || !kv->kv_indptr || !kv->prefix_len) return EAGLE3_E_NULL;
+  if (!dkv->k || !dkv->v || !dkv->k[0] || !dkv->v[0] || !dkv->kv_indptr || !dkv->prefix_len) return EAGLE3_E_NULL;
+  if (!ctx->ws || !ctx->has_target || !ctx->has_draft) return EAGLE3_E_STATE;
+  const eagle3_config& c = ctx->cfg;
+  if (T < 1 || kv->max_prefix_len < 0 || dkv->max_prefix_len < 0) return EAGLE3_E_SHAPE;
+  for (int l = 0; l < c.n_layers; ++l)
+    if (!kv->k[l] || !kv->v[l]) return EAGLE3_E_NULL;
+  hipStream_t st = (hipStream_t)stream;
+  const int k = c.hidden, H = c.n_heads, Hkv = c.n_kv_heads, d = c.head_dim, C = ctx->chunk_max;
+  const eagle3_layer_weights& w = ctx->dw.layer;
+  CK(launch_chain_parent(ctx->chain_parent, std::min(C, 64), st));
+  int done_draft = 0;
+  for (int c0 = 0; c0 < T; c0 += C) {
+    const int n = std::min(C, T - c0);
+    const bool last = c0 + n == T;
+    // target: the chunk as a chain on top of everything cached so far; features of every position recorded
+    eagle3_kv kvc = *kv;
+    kvc.max_prefix_len = kv->max_prefix_len + c0;
+    const size_t nk = (size_t)n * k;
+    TRY(verify_layers(ctx, 1, n, tokens + c0, ctx->chain_parent, &kvc, nullptr, 0, c.n_layers, nullptr, nullptr,
+                      ctx->chunk_taps, nullptr, st));
+    CK(launch_advance_lengths((int32_t*)kv->prefix_len, 1, n, st));
+    if (last) {                                       // next-token logits of the last position only
+      CK(launch_add_norm(ctx->bf16, ctx->x + (size_t)(n - 1) * k, nullptr, 0, 1, k, ctx->tw.final_norm, c.rms_eps, ctx->act_k,
+                         nullptr, st));
+      GemmWeights Wlm = {{ctx->tw.lm_head, nullptr, nullptr}, {c.vocab, 0, 0}, 1, 0};
+      TRY(ctx->project(ctx->act_k, Wlm, 1, c.vocab, k, GEMM_EPI_PARTIAL, nullptr, st, logits_last));
+    }
+    // fused features of the chunk's positions; the draft cache rows of those whose next token is known
+    TRY(fuse_rows(ctx, ctx->chunk_taps, ctx->chunk_taps + nk, ctx->chunk_taps + 2 * nk, n, ctx->chunk_g, st));
+    if (last) CK(hipMemcpyAsync(g_last, ctx->chunk_g + (size_t)(n - 1) * k, (size_t)k * sizeof(float), hipMemcpyDeviceToDevice, st));
+    const int m = last ? n - 1 : n;
+    if (m > 0) {
+      CK(launch_draft_prep1(dkv->kv_indptr, dkv->prefix_len, m, ctx->pos1, ctx->slot, ctx->mask, ctx->seq, st));
+      CK(launch_draft_input(ctx->bf16, ctx->tw.embed, c.vocab, tokens + c0 + 1, ctx->chunk_g, nullptr, m, k, ctx->dw.norm_embed,
+                            ctx->dw.norm_feat, c.rms_eps, ctx->act_k, ctx->x, ctx->pos1, d, c.rope_theta, ctx->cs, st));
+      GemmWeights Wqkv = {{w.wq, w.wk, w.wv}, {H * d, Hkv * d, Hkv * d}, 3, 0};
+      int S_qkv = 1;
+      TRY(ctx->project(ctx->act_k, Wqkv, m, (H + 2 * Hkv) * d, 2 * k, GEMM_EPI_PARTIAL, &S_qkv, st));
+      CK(launch_rope_kv_write(ctx->bf16, ctx->part, S_qkv, m, H, Hkv, d, ctx->cs, ctx->slot, ctx->q, dkv->k[0], dkv->v[0], st));
+      CK(launch_advance_lengths((int32_t*)dkv->prefix_len, 1, m, st));
+      done_draft += m;
+    }
+  }
+  (void)done_draft;
   return EAGLE3_OK;
 }
 

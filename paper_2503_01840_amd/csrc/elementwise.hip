@@ -265,7 +265,26 @@ __global__ __launch_bounds__(64) void draft_prep1_kernel(const int32_t* __restri
   if (j == 0) { seq[0].kv_base = base; seq[0].n_prefix = P; seq[0].n_tail = n_new; seq[0].order = 0; }
 }
 
+// parent[i] = i - 1: a chain (ordinary causal decoding as a tree)
+__global__ __launch_bounds__(64) void chain_parent_kernel(int32_t* __restrict__ parent, int n) {
+  if ((int)threadIdx.x < n) parent[threadIdx.x] = (int)threadIdx.x - 1;
+}
+__global__ __launch_bounds__(64) void advance_lengths_kernel(int32_t* __restrict__ len, int B, int by) {
+  const int b = blockIdx.x * 64 + threadIdx.x;
+  if (b < B) len[b] += by;
+}
+
 }  // namespace
+
+hipError_t launch_chain_parent(int32_t* parent, int n, hipStream_t st) {
+  if (n > 64) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(chain_parent_kernel, dim3(1), dim3(64), 0, st, parent, n);
+  return hipGetLastError();
+}
+hipError_t launch_advance_lengths(int32_t* len, int B, int by, hipStream_t st) {
+  hipLaunchKernelGGL(advance_lengths_kernel, dim3((B + 63) / 64), dim3(64), 0, st, len, B, by);
+  return hipGetLastError();
+}
 
 #define DISPATCH_BF16(flag, KERNEL, grid, block, st, ...)                                       \
   do {                                                                                          \

@@ -71,6 +71,9 @@ hipError_t launch_draft_input(bool bf16, const void* embed, int vocab, const int
 hipError_t launch_draft_prep1(const int32_t* kv_indptr, const int32_t* prefix_len, int n_new, int32_t* pos, int32_t* slot,
                               uint32_t* mask, SeqInfo* seq, hipStream_t st);
 
+hipError_t launch_chain_parent(int32_t* parent, int n, hipStream_t st);                 // parent[i] = i - 1
+hipError_t launch_advance_lengths(int32_t* len, int B, int by, hipStream_t st);          // len[b] += by
+
 // ---------------------------------------------------------------- attention (attention.hip)
 // Tree-masked attention of rows [B * rows_per_seq] against a (ragged) cache.
 //   bf16: q [R,H,d] bf16, cache bf16, out = fragment-major bf16 [R, H*d]; d must be 128.

@@ -143,3 +143,43 @@ def test_commit_moves_rows_in_every_layer_for_a_ragged_batch():
             for cur, old in ((ks[l], k0[l]), (vs[l], v0[l])):
                 assert torch.equal(cur[first:first + len(p)], old[first + torch.as_tensor(p, device=DEV)]), (b, l)
                 assert torch.equal(cur[int(indptr[b]):first], old[int(indptr[b]):first])   # the context did not move
+
+
+@pytest.mark.parametrize("chunk", [64, 24])
+def test_prefill_builds_caches_features_and_the_draft_context(chunk):
+    """eagle3_prefill against the oracle's prefill (tiny fp32 model, 64-token prompt; one chunk of 64, and chunks of
+    24 + 24 + 16): target cache of every layer, draft cache, fused feature and logits of the last position; then
+    decoding continues from the GPU-built state and still equals plain greedy decoding."""
+    import paper_2503_01840_amd as E
+    shape = S.get_shape("c1")
+    D, K, N = shape.depth, shape.topk, min(chunk, 30)
+    model = PL.OracleModel(shape)
+    inp = PL.real_prefill_inputs(shape, model)
+    prompt, pre, P = inp["prefix_tok"], inp["prefill"], inp["P"]
+    ctx = E.Eagle3Context(shape, max_batch=1, max_nodes=chunk, max_depth=D, max_topk=K, max_new=chunk, device=DEV)
+    W = PL.device_weights(shape, device=DEV)
+    ctx.set_weights(W["target"], W["draft"])
+    cap = P + 8 * (D + 1) + 64
+    z = lambda: torch.zeros(cap, shape.n_kv_heads, shape.head_dim, dtype=torch.float32, device=DEV)
+    ks, vs = [z() for _ in range(shape.n_layers)], [z() for _ in range(shape.n_layers)]
+    i32 = lambda v: torch.tensor(v, dtype=torch.int32, device=DEV)
+    kv = E.KVCache(ks, vs, i32([0, cap]), i32([0]), 0)
+    dkv = E.KVCache([z()], [z()], i32([0, cap]), i32([0]), 0)
+    g_last, logits = E.eagle3_prefill(ctx, torch.as_tensor(prompt, dtype=torch.int32, device=DEV), kv, dkv)
+    torch.cuda.synchronize()
+    assert int(kv.prefix_len[0]) == P and int(dkv.prefix_len[0]) == P - 1
+    for l in range(shape.n_layers):
+        assert np.max(np.abs(ks[l][:P].cpu().numpy() - pre["k_new"][l])) < 1e-4, l
+        assert np.max(np.abs(vs[l][:P].cpu().numpy() - pre["v_new"][l])) < 1e-4, l
+    assert np.max(np.abs(logits.cpu().numpy() - pre["logits"][-1])) < 1e-4
+    assert np.max(np.abs(g_last.cpu().numpy() - inp["g_new"][0].numpy())) < 1e-4
+    Kd, Vd = inp["draft_kv"]
+    assert np.max(np.abs(dkv.k_layers[0][:P - 1].cpu().numpy() - Kd.numpy())) < 1e-4
+    assert np.max(np.abs(dkv.v_layers[0][:P - 1].cpu().numpy() - Vd.numpy())) < 1e-4
+    # go on decoding from this state
+    root = int(torch.argmax(logits))
+    assert root == int(inp["tok_new"][0])
+    ref = O.greedy_decode(shape, model.layer, model.globals(), prompt, 24)
+    state = {"kv": kv, "dkv": dkv, "g_new": g_last[None].contiguous(), "tok_new": i32([root]), "P": P, "Pd": P - 1}
+    emitted, accept_lens, _ = gpu_decode(E, ctx, shape, state, 5, D, K, N, planted_hook(ref, [2, 1, 0, 2]))
+    assert emitted == ref[:len(emitted)] and max(accept_lens) >= 2

@@ -410,6 +410,21 @@ def draft_expand(shape, dw, embed, g_new, tok_new, K_cache, V_cache, n_ctx, dept
     }
 
 
+def draft_chains(shape, dw, embed, g_new, tok_new, caches, n_ctx, length, rounding="none"):
+    """Chain drafting for a batch (Section 4.3 / 4.4: chains of 2-3 draft tokens, no tree, at large batch sizes):
+    every sequence independently runs the draft steps of Section 3.1 with ONE proposal per step, i.e. the
+    expansion above with top-k 1.  g_new[b] [n_b, k], tok_new[b] [n_b], caches[b] = (K, V) draft cache arrays
+    (extended in place), n_ctx[b] valid entries.  Returns (chain_tok [B, length+1] with the root first,
+    chain_logp [B, length+1] cumulative)."""
+    toks, logps = [], []
+    for b in range(len(g_new)):
+        t = draft_expand(shape, dw, embed, np.asarray(g_new[b], dtype=np.float64), np.asarray(tok_new[b]),
+                         caches[b][0], caches[b][1], int(n_ctx[b]), length, 1, length + 1, rounding=rounding)
+        assert np.array_equal(t["parent"], np.arange(-1, length))
+        toks.append(t["tree_tok"]); logps.append(t["score"])
+    return np.stack(toks), np.stack(logps)
+
+
 # ----------------------------------------------------------------------------- acceptance
 
 def _children(parent, node):

@@ -10,6 +10,7 @@ from transformers.models.llama.modeling_llama import (LlamaAttention, LlamaMLP, 
 import eagle3_synth as S
 from oracle import eagle3_oracle as O
 from hf_llama import hf_config
+import pipeline as PL
 
 SMALL = S.get_shape("c1").with_(name="small", hidden=128, n_heads=4, n_kv_heads=2, head_dim=32, intermediate=176,
                                 vocab=512, draft_vocab=384, n_layers=2)
@@ -250,3 +251,35 @@ def test_follow_mode_accepts_near_tie_swaps_and_rejects_real_errors():
                        follow={"pool_tok": pt[:K + 1], "frontier": [], "chosen": np.arange(1, K + 1)}, tol=gap * 2)
     except AssertionError as e:  # pragma: no cover
         pytest.fail(str(e))
+
+
+def test_batched_chains_are_the_per_sequence_greedy_draft_chains():
+    """draft_chains (the batched chain mode of the serving experiments) against a direct statement: per sequence,
+    repeatedly run the draft layer on (previous output, previous arg-max token) and take the arg-max."""
+    shape = S.get_shape("c1")
+    model = PL.OracleModel(shape)
+    dw, emb = model.draft(), model.globals()["embed"]
+    rs = np.random.RandomState(4)
+    B, L = 3, 3
+    n_ctx, n_new = [5, 0, 9], [1, 2, 3]
+    g = [rs.randn(n, shape.hidden) for n in n_new]
+    tok = [rs.randint(0, shape.vocab, n) for n in n_new]
+    ctxs = [(rs.randn(c + 8, shape.n_kv_heads, shape.head_dim), rs.randn(c + 8, shape.n_kv_heads, shape.head_dim)) for c in n_ctx]
+    copies = [(k.copy(), v.copy()) for k, v in ctxs]
+    chain_tok, chain_logp = O.draft_chains(shape, dw, emb, g, tok, ctxs, n_ctx, L)
+    ident = lambda a: a
+    for b in range(B):
+        K, V = copies[b]
+        n, c = n_new[b], n_ctx[b]
+        a, z = O.draft_forward(shape, dw, emb, g[b], tok[b], c + np.arange(n), K, V, c, c, np.tril(np.ones((n, n), dtype=bool)), ident)
+        feat, lp, cum, want = a[-1], O.log_softmax(z[-1]), 0.0, [int(tok[b][-1])]
+        for lvl in range(1, L + 1):
+            t = int(np.argmax(lp)); cum += lp[t]; want.append(int(dw["d2t"][t]))
+            assert chain_logp[b, lvl] == pytest.approx(cum, abs=1e-12)
+            if lvl == L:
+                break
+            vis = np.ones((1, lvl), dtype=bool)
+            a, z = O.draft_forward(shape, dw, emb, feat[None], np.array([want[-1]]), np.array([c + n - 1 + lvl]), K, V,
+                                   c + n, c + n + lvl - 1, vis, ident)
+            feat, lp = a[0], O.log_softmax(z[0])
+        assert chain_tok[b].tolist() == want

@@ -190,6 +190,23 @@ int eagle3_accept(eagle3_ctx* ctx, int32_t B, int32_t N, const float* logits, co
                   const int32_t* parent, float temperature, const float* uniforms,
                   int32_t* accept_len, int32_t* path, int32_t* bonus_tok, eagle3_stream stream);
 
+/* Chain drafting for a batch (Section 4.3 / 4.4: at large batch sizes the serving experiments draft a chain of 2-3
+ * tokens per sequence instead of a tree).  The draft steps of Section 3.1 with one proposal per step: forward 1 runs,
+ * for every sequence b, the rows (g_new[b][j], tok_new[b][j]), j < n_new[b] (the positions accepted by the previous
+ * step, causal among themselves); its last row gives the first drafted token (arg-max of the draft distribution,
+ * ties -> smaller id); every further forward runs one row per sequence, (previous output a, previous token).
+ *   g_new      fp32 [B, rows1, hidden], tok_new int32 [B, rows1] (target ids), n_new DEVICE int32 [B] with
+ *              1 <= n_new[b] <= rows1; rows j >= n_new[b] are padding (read, never used)
+ *   draft_kv   one layer, B sequences (ragged): forward 1 appends rows1 slots per sequence of which the first
+ *              n_new[b] stay valid, the later forwards overwrite the slots after those; prefix_len is not changed
+ *   chain_tok  int32 [B, length + 1]: [b][0] = the root tok_new[b][n_new[b]-1], [b][l] = the l-th drafted token
+ *              (target id); with parent[l] = l - 1 this is the tree eagle3_tree_verify takes
+ *   chain_logp fp32 [B, length + 1]: cumulative log-probability ([b][0] = 0)
+ * Requires 1 <= B <= max_batch, 1 <= rows1 <= min(max_new, max_nodes), 1 <= length <= max_depth. */
+int eagle3_draft_chain(eagle3_ctx* ctx, int32_t B, const float* g_new, const int32_t* tok_new, const int32_t* n_new,
+                       int32_t rows1, const eagle3_kv* draft_kv, int32_t length, int32_t* chain_tok, float* chain_logp,
+                       eagle3_stream stream);
+
 /* Section 3.1, first paragraph of the pipeline: during the prefill phase the target model runs over the prompt, the
  * low / mid / high feature sequences of its positions are recorded and fused, and the draft model's context is built
  * from them.  One sequence.  The T prompt tokens are run through every target layer in chunks of

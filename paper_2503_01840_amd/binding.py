@@ -17,7 +17,7 @@ EAGLE3_FP32, EAGLE3_BF16 = 0, 1
 EXPORTS = ["eagle3_create", "eagle3_destroy", "eagle3_workspace_bytes", "eagle3_set_workspace", "eagle3_set_weights",
            "eagle3_strerror", "eagle3_last_error", "eagle3_profile_begin", "eagle3_profile_read", "eagle3_profile_end",
            "eagle3_fuse_features", "eagle3_draft_expand",
-           "eagle3_tree_verify", "eagle3_tree_verify_layers", "eagle3_accept", "eagle3_accept_static", "eagle3_commit", "eagle3_prefill"]
+           "eagle3_tree_verify", "eagle3_tree_verify_layers", "eagle3_accept", "eagle3_accept_static", "eagle3_commit", "eagle3_prefill", "eagle3_draft_chain"]
 
 
 class Config(C.Structure):
@@ -90,6 +90,8 @@ def lib():
                                     C.c_void_p]
         L.eagle3_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(KV), C.POINTER(KV), C.c_void_p, C.c_void_p,
                                      C.c_void_p]
+        L.eagle3_draft_chain.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(KV),
+                                         C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -341,3 +343,16 @@ def eagle3_prefill(ctx, tokens, kv, draft_kv):
     kv.set_max_prefix_len(kv.max_prefix_len + T)
     draft_kv.set_max_prefix_len(draft_kv.max_prefix_len + T - 1)
     return g_last, logits
+
+
+def eagle3_draft_chain(ctx, g_new, tok_new, n_new, draft_kv, length):
+    """Batched chain drafting.  g_new [B, rows1, k], tok_new [B, rows1], n_new [B].  Returns (chain_tok [B, length+1],
+    chain_logp [B, length+1])."""
+    B, rows1 = tok_new.shape
+    dev = tok_new.device
+    chain_tok = torch.empty(B, length + 1, dtype=torch.int32, device=dev)
+    chain_logp = torch.empty(B, length + 1, dtype=torch.float32, device=dev)
+    _check(lib().eagle3_draft_chain(ctx._h, B, _ptr(g_new, torch.float32), _ptr(tok_new, torch.int32),
+                                    _ptr(n_new, torch.int32), rows1, C.byref(draft_kv.c), int(length), _ptr(chain_tok),
+                                    _ptr(chain_logp), _stream()))
+    return chain_tok, chain_logp

@@ -68,6 +68,8 @@ struct eagle3_ctx {
   float* z; float* a_buf; int32_t* pos1; float* topk_scratch; DraftState ds;
   int chunk_max;                        // rows per prefill chunk
   int32_t* chain_parent; float* chunk_taps; float* chunk_g;
+  int rows1_max;                        // rows per sequence of a chain batch's forward 1
+  ChainState cs_chain;
 
   void carve(void* base) {
     const eagle3_config& c = cfg;
@@ -87,10 +89,20 @@ struct eagle3_ctx {
     cs = cv.take<float>((size_t)Rall * c.head_dim);
     seq = cv.take<SeqInfo>(std::max(c.max_batch, 1));
     accept_stats = cv.take<float>(accept_scratch_floats(R_max, c.vocab));
-    z = cv.take<float>((size_t)Md_max * c.draft_vocab);
-    a_buf = cv.take<float>((size_t)a_rows * k);
-    pos1 = cv.take<int32_t>(Md_max);
-    topk_scratch = cv.take<float>(topk_scratch_floats(c.max_topk, c.draft_vocab, c.max_topk));
+    const int mb = std::max(c.max_batch, 1);
+    z = cv.take<float>((size_t)std::max(Md_max, mb) * c.draft_vocab);
+    a_buf = cv.take<float>((size_t)std::max(a_rows, mb * rows1_max) * k);
+    pos1 = cv.take<int32_t>(Rall);
+    topk_scratch = cv.take<float>(std::max(topk_scratch_floats(c.max_topk, c.draft_vocab, c.max_topk),
+                                           topk_scratch_floats(mb, c.draft_vocab, 1)));
+    cs_chain.top_val = cv.take<float>(mb);
+    cs_chain.top_idx = cv.take<int32_t>(mb);
+    cs_chain.row_tok = cv.take<int32_t>(mb);
+    cs_chain.row_src = cv.take<int32_t>(mb);
+    cs_chain.row_pos = cv.take<int32_t>(mb);
+    cs_chain.row_slot = cv.take<int32_t>(mb);
+    cs_chain.row_mask = cv.take<uint32_t>((size_t)mb * 4);
+    cs_chain.seq = cv.take<SeqInfo>(mb);
     ds.pool_tok = cv.take<int32_t>(pool_max);
     ds.pool_parent = cv.take<int32_t>(pool_max);
     ds.pool_depth = cv.take<int32_t>(pool_max);
@@ -200,6 +212,7 @@ int eagle3_create(const eagle3_config* cfg, eagle3_ctx** out) {
   ctx->Rall = std::max(ctx->R_max, ctx->Md_max);
   ctx->a_rows = c.max_new + (c.max_depth - 1) * c.max_topk;
   ctx->chunk_max = std::min(c.max_nodes, c.max_new);
+  ctx->rows1_max = std::min(c.max_nodes, c.max_new);
   ctx->pool_max = 1 + c.max_topk + (c.max_depth - 1) * c.max_topk * c.max_topk;
   const size_t widest = std::max<size_t>({(size_t)(c.n_heads + 2 * c.n_kv_heads) * c.head_dim, (size_t)c.hidden,
                                           ctx->bf16 ? (size_t)0 : (size_t)2 * c.intermediate});
@@ -504,6 +517,61 @@ int eagle3_accept(eagle3_ctx* ctx, int32_t B, int32_t N, const float* logits, co
   if (B < 1 || B > ctx->cfg.max_batch || N < 1 || N > ctx->cfg.max_nodes || !(temperature >= 0.f)) return EAGLE3_E_SHAPE;
   CK(launch_accept(logits, tree_tok, parent, B, N, ctx->cfg.vocab, temperature, uniforms, ctx->accept_stats, accept_len,
                    path, bonus_tok, (hipStream_t)stream));
+  return EAGLE3_OK;
+}
+
+int eagle3_draft_chain(eagle3_ctx* ctx, int32_t B, const float* g_new, const int32_t* tok_new, const int32_t* n_new,
+                       int32_t rows1, const eagle3_kv* dkv, int32_t length, int32_t* chain_tok, float* chain_logp,
+                       eagle3_stream stream) {
+  if (!ctx || !g_new || !tok_new || !n_new || !dkv || !chain_tok || !chain_logp) return EAGLE3_E_NULL;
+  if (!dkv->k || !dkv->v || !dkv->k[0] || !dkv->v[0] || !dkv->kv_indptr || !dkv->prefix_len) return EAGLE3_E_NULL;
+  if (!ctx->ws || !ctx->has_draft || !ctx->has_target) return EAGLE3_E_STATE;
+  const eagle3_config& c = ctx->cfg;
+  if (B < 1 || B > c.max_batch || rows1 < 1 || rows1 > ctx->rows1_max || length < 1 || length > c.max_depth ||
+      dkv->max_prefix_len < 0)
+    return EAGLE3_E_SHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  const int k = c.hidden, H = c.n_heads, Hkv = c.n_kv_heads, d = c.head_dim, Vd = c.draft_vocab;
+  const eagle3_layer_weights& w = ctx->dw.layer;
+  const ChainState& cs = ctx->cs_chain;
+  void* kc = dkv->k[0];
+  void* vc = dkv->v[0];
+  for (int level = 1; level <= length; ++level) {
+    const int rps = level == 1 ? rows1 : 1, M = B * rps;
+    const int32_t *pos, *slot;
+    const uint32_t* mask;
+    const SeqInfo* seq;
+    if (level == 1) {
+      CK(launch_chain_prep1(dkv->kv_indptr, dkv->prefix_len, B, rows1, ctx->pos1, ctx->slot, ctx->mask, ctx->seq, st));
+      pos = ctx->pos1; slot = ctx->slot; mask = ctx->mask; seq = ctx->seq;
+      CK(launch_draft_input(ctx->bf16, ctx->tw.embed, c.vocab, tok_new, g_new, nullptr, M, k, ctx->dw.norm_embed,
+                            ctx->dw.norm_feat, c.rms_eps, ctx->act_k, ctx->x, pos, d, c.rope_theta, ctx->cs, st));
+    } else {
+      pos = cs.row_pos; slot = cs.row_slot; mask = cs.row_mask; seq = cs.seq;
+      CK(launch_draft_input(ctx->bf16, ctx->tw.embed, c.vocab, cs.row_tok, ctx->a_buf, cs.row_src, M, k, ctx->dw.norm_embed,
+                            ctx->dw.norm_feat, c.rms_eps, ctx->act_k, ctx->x, pos, d, c.rope_theta, ctx->cs, st));
+    }
+    const int max_len = dkv->max_prefix_len + rows1 + level;
+    GemmWeights Wqkv = {{w.wq, w.wk, w.wv}, {H * d, Hkv * d, Hkv * d}, 3, 0};
+    int S_qkv = 1, S_down = 1;
+    TRY(ctx->project(ctx->act_k, Wqkv, M, (H + 2 * Hkv) * d, 2 * k, GEMM_EPI_PARTIAL, &S_qkv, st));
+    TRY(layer_tail(ctx, w, B, rps, S_qkv, slot, ctx->cs, mask, seq, kc, vc, max_len, &S_down, st));
+    if (level == 1 && rows1 > 1) {
+      // a = y1 + MLP(...) for every row, then the row of each sequence's last real position moves to row b
+      CK(launch_add_norm(ctx->bf16, ctx->x, ctx->part, S_down, M, k, nullptr, c.rms_eps, nullptr, nullptr, st));
+      CK(launch_chain_gather(ctx->x, n_new, B, rows1, k, ctx->a_buf, st));
+      CK(hipMemcpyAsync(ctx->x, ctx->a_buf, (size_t)B * k * sizeof(float), hipMemcpyDeviceToDevice, st));
+      CK(launch_add_norm(ctx->bf16, ctx->x, nullptr, 0, B, k, ctx->dw.final_norm, c.rms_eps, ctx->act_k, nullptr, st));
+    } else {
+      float* copies[4] = {ctx->a_buf, nullptr, nullptr, nullptr};
+      CK(launch_add_norm(ctx->bf16, ctx->x, ctx->part, S_down, B, k, ctx->dw.final_norm, c.rms_eps, ctx->act_k, copies, st));
+    }
+    GemmWeights Wlm = {{ctx->dw.lm_head, nullptr, nullptr}, {Vd, 0, 0}, 1, 0};
+    TRY(ctx->project(ctx->act_k, Wlm, B, Vd, k, GEMM_EPI_PARTIAL, nullptr, st, ctx->z));
+    CK(launch_topk_rows(ctx->z, Vd, 0, B, Vd, 1, ctx->topk_scratch, cs.top_val, cs.top_idx, st));
+    CK(launch_chain_select(cs, ctx->dw.d2t, dkv->kv_indptr, dkv->prefix_len, n_new, tok_new, B, rows1, level, length,
+                           chain_tok, chain_logp, st));
+  }
   return EAGLE3_OK;
 }
 

@@ -117,6 +117,24 @@ hipError_t launch_draft_rerank(const DraftState& s, const int32_t* d2t, const in
                                int n_nodes, int32_t* tree_tok, int32_t* parent, int32_t* node_depth, float* cum_logprob,
                                int32_t* chosen_dbg, hipStream_t st);
 
+// Batched chain drafting: per-sequence state of the next forward (one row per sequence), device arrays.
+struct ChainState {
+  float* top_val;            // [B] log-probability of the top-1 token of every sequence's last row
+  int32_t* top_idx;          // [B] its draft id
+  int32_t* row_tok;          // [B] target ids
+  int32_t* row_src;          // [B]
+  int32_t* row_pos;          // [B]
+  int32_t* row_slot;         // [B]
+  uint32_t* row_mask;        // [B][4]
+  SeqInfo* seq;              // [B]
+};
+hipError_t launch_chain_prep1(const int32_t* kv_indptr, const int32_t* prefix_len, int B, int rows1, int32_t* pos,
+                              int32_t* slot, uint32_t* mask, SeqInfo* seq, hipStream_t st);
+hipError_t launch_chain_select(const ChainState& s, const int32_t* d2t, const int32_t* kv_indptr, const int32_t* prefix_len,
+                               const int32_t* n_new, const int32_t* tok_new, int B, int rows1, int level, int length,
+                               int32_t* chain_tok, float* chain_logp, hipStream_t st);
+hipError_t launch_chain_gather(const float* x, const int32_t* n_new, int B, int rows1, int k, float* x_out, hipStream_t st);
+
 // ---------------------------------------------------------------- acceptance (accept.hip)
 #define ACCEPT_CHUNK 2048
 size_t accept_scratch_floats(int R, int V);

@@ -256,7 +256,100 @@ __global__ __launch_bounds__(1024) void draft_rerank_kernel(DraftState s, const 
   }
 }
 
+// ---------------------------------------------------------------------------------------------- batched chains
+// Chain drafting for a batch (top-1 per level, no tree): forward 1 runs rows1 rows per sequence (the n_new[b] <= rows1
+// positions accepted by the previous step, the rest padding), every later forward one row per sequence.
+
+// Rows of forward 1: row (b, j) sits at position P_b + j, cache slot base_b + P_b + j, and sees the draft context plus
+// rows 0..j of its own sequence.  Padding rows (j >= n_new[b]) see the same (their results are never used; their
+// cache rows land in slots that later forwards overwrite or that stay invisible).
+__global__ __launch_bounds__(64) void chain_prep1_kernel(const int32_t* __restrict__ kv_indptr,
+                                                        const int32_t* __restrict__ prefix_len, int B, int rows1,
+                                                        int32_t* __restrict__ pos, int32_t* __restrict__ slot,
+                                                        uint32_t* __restrict__ mask, SeqInfo* __restrict__ seq) {
+  const int b = blockIdx.x, j = threadIdx.x;
+  const int P = prefix_len[b], base = kv_indptr[b];
+  if (j < rows1) {
+    const int r = b * rows1 + j;
+    pos[r] = P + j;
+    slot[r] = base + P + j;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int lo = 32 * w;
+      mask[r * 4 + w] = j < lo ? 0u : (j - lo >= 31 ? 0xFFFFFFFFu : ((2u << (j - lo)) - 1u));
+    }
+  }
+  if (j == 0) { seq[b].kv_base = base; seq[b].n_prefix = P; seq[b].n_tail = rows1; seq[b].order = b; }
+}
+
+// After forward `level` (1-based) of a chain batch: the top-1 token of every sequence's last row extends its chain;
+// when level < length, the inputs of the next forward (one row per sequence) are written.
+__global__ __launch_bounds__(64) void chain_select_kernel(ChainState s, const int32_t* __restrict__ d2t,
+                                                         const int32_t* __restrict__ kv_indptr,
+                                                         const int32_t* __restrict__ prefix_len,
+                                                         const int32_t* __restrict__ n_new,
+                                                         const int32_t* __restrict__ tok_new, int B, int rows1, int level,
+                                                         int length, int32_t* __restrict__ chain_tok,
+                                                         float* __restrict__ chain_logp) {
+  const int b = blockIdx.x * 64 + threadIdx.x;
+  if (b >= B) return;
+  const int n = min(max(n_new[b], 1), rows1);
+  if (level == 1) {                                  // entry 0 of a chain: its root, the last sampled token
+    chain_tok[b * (length + 1)] = tok_new[b * rows1 + n - 1];
+    chain_logp[b * (length + 1)] = 0.f;
+  }
+  const int tok = d2t[s.top_idx[b]];
+  const float cum = (level == 1 ? 0.f : chain_logp[b * (length + 1) + level - 1]) + s.top_val[b];
+  chain_tok[b * (length + 1) + level] = tok;
+  chain_logp[b * (length + 1) + level] = cum;
+  if (level >= length) return;
+  const int P = prefix_len[b], base = kv_indptr[b];
+  s.row_tok[b] = tok;
+  s.row_src[b] = b;                                  // the gathered / previous output row of this sequence
+  s.row_pos[b] = P + n - 1 + level;
+  s.row_slot[b] = base + P + n + (level - 1);
+  const int tail = level;                            // chain rows visible to the new row, itself included
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const int lo = 32 * w;
+    s.row_mask[b * 4 + w] = tail <= lo ? 0u : (tail - lo >= 32 ? 0xFFFFFFFFu : ((1u << (tail - lo)) - 1u));
+  }
+  s.seq[b].kv_base = base;
+  s.seq[b].n_prefix = P + n;
+  s.seq[b].n_tail = level;
+  s.seq[b].order = b;
+}
+
+// x_out[b] = x[b * rows1 + n_new[b] - 1]: the output row of every sequence's last real position.
+__global__ __launch_bounds__(256) void chain_gather_kernel(const float* __restrict__ x, const int32_t* __restrict__ n_new,
+                                                          int rows1, int k, float* __restrict__ x_out) {
+  const int b = blockIdx.x;
+  const int n = min(max(n_new[b], 1), rows1);
+  const float4* src = (const float4*)(x + ((size_t)b * rows1 + n - 1) * k);
+  float4* dst = (float4*)(x_out + (size_t)b * k);
+  for (int c = threadIdx.x; c < k / 4; c += 256) dst[c] = src[c];
+}
+
 }  // namespace
+
+hipError_t launch_chain_prep1(const int32_t* kv_indptr, const int32_t* prefix_len, int B, int rows1, int32_t* pos,
+                              int32_t* slot, uint32_t* mask, SeqInfo* seq, hipStream_t st) {
+  if (rows1 < 1 || rows1 > 64) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(chain_prep1_kernel, dim3(B), dim3(64), 0, st, kv_indptr, prefix_len, B, rows1, pos, slot, mask, seq);
+  return hipGetLastError();
+}
+hipError_t launch_chain_select(const ChainState& s, const int32_t* d2t, const int32_t* kv_indptr, const int32_t* prefix_len,
+                               const int32_t* n_new, const int32_t* tok_new, int B, int rows1, int level, int length,
+                               int32_t* chain_tok, float* chain_logp, hipStream_t st) {
+  if (length > 120) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(chain_select_kernel, dim3((B + 63) / 64), dim3(64), 0, st, s, d2t, kv_indptr, prefix_len, n_new, tok_new, B,
+                     rows1, level, length, chain_tok, chain_logp);
+  return hipGetLastError();
+}
+hipError_t launch_chain_gather(const float* x, const int32_t* n_new, int B, int rows1, int k, float* x_out, hipStream_t st) {
+  hipLaunchKernelGGL(chain_gather_kernel, dim3(B), dim3(256), 0, st, x, n_new, rows1, k, x_out);
+  return hipGetLastError();
+}
 
 size_t topk_scratch_floats(int n_rows, int V, int K) {
   const size_t n_spans = (size_t)(V + TOPK_SPAN - 1) / TOPK_SPAN;

@@ -183,3 +183,59 @@ def test_prefill_builds_caches_features_and_the_draft_context(chunk):
     state = {"kv": kv, "dkv": dkv, "g_new": g_last[None].contiguous(), "tok_new": i32([root]), "P": P, "Pd": P - 1}
     emitted, accept_lens, _ = gpu_decode(E, ctx, shape, state, 5, D, K, N, planted_hook(ref, [2, 1, 0, 2]))
     assert emitted == ref[:len(emitted)] and max(accept_lens) >= 2
+
+
+def _chain_case(E, shape, B, rows1, L, seed, tol):
+    model = PL.OracleModel(shape)
+    dw, emb = model.draft(), model.globals()["embed"]
+    rs = np.random.RandomState(seed)
+    n_ctx = rs.randint(0, 90, B)
+    n_ctx[0] = 0                                         # one sequence with an empty draft context
+    n_new = rs.randint(1, rows1 + 1, B)
+    n_new[-1] = rows1
+    dt = torch.float32 if shape.dtype == "fp32" else torch.bfloat16
+    g = S.normal(S.SEED + seed, S.TensorIds.G_NEW, (B, rows1, shape.hidden))
+    tok = S.uniform_ints(S.SEED + seed, S.TensorIds.TOK_NEW, (B, rows1), 0, shape.vocab)
+    cap = rows1 + L + 2
+    indptr = np.zeros(B + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum(n_ctx + cap)
+    total = int(indptr[-1])
+    K_all, V_all = S.kv_layer(shape, 0, total, seed=S.SEED + seed, draft=True)
+    ctx = E.Eagle3Context(shape, max_batch=B, max_nodes=max(rows1, L + 1, 8), max_depth=max(L, 2), max_topk=4, max_new=max(rows1, 2),
+                          device=DEV)
+    W = PL.device_weights(shape, device=DEV)
+    ctx.set_weights(W["target"], W["draft"])
+    Kd, Vd = K_all.to(DEV), V_all.to(DEV)
+    dkv = E.KVCache([Kd], [Vd], torch.as_tensor(indptr, dtype=torch.int32, device=DEV),
+                    torch.as_tensor(n_ctx, dtype=torch.int32, device=DEV), int(n_ctx.max()))
+    chain_tok, chain_logp = E.eagle3_draft_chain(ctx, g.to(DEV), tok.to(DEV), torch.as_tensor(n_new, dtype=torch.int32, device=DEV),
+                                                 dkv, L)
+    torch.cuda.synchronize()
+    caches = []
+    for b in range(B):
+        lo = int(indptr[b])
+        Kc = np.zeros((int(n_ctx[b]) + cap, shape.n_kv_heads, shape.head_dim)); Vc = np.zeros_like(Kc)
+        Kc[:n_ctx[b]] = O.as_f64(K_all[lo:lo + n_ctx[b]]); Vc[:n_ctx[b]] = O.as_f64(V_all[lo:lo + n_ctx[b]])
+        caches.append((Kc, Vc))
+    ref_tok, ref_logp = O.draft_chains(shape, dw, emb, [O.as_f64(g[b, :n_new[b]]) for b in range(B)],
+                                       [tok[b, :n_new[b]].numpy().astype(np.int64) for b in range(B)], caches, n_ctx, L,
+                                       rounding=model.rounding)
+    got_tok, got_logp = chain_tok.cpu().numpy(), chain_logp.cpu().numpy()
+    # arg-max margins of the oracle decide whether a differing token is a near-tie; none is expected at these sizes
+    assert np.array_equal(got_tok, ref_tok), (got_tok, ref_tok)
+    assert np.max(np.abs(got_logp - ref_logp)) < tol * L
+    for b in range(B):                                   # the cache rows of the real positions and of the chain
+        lo, c, n = int(indptr[b]), int(n_ctx[b]), int(n_new[b])
+        rows = slice(lo + c, lo + c + n + L - 1)
+        assert np.max(np.abs(Kd[rows].float().cpu().numpy() - caches[b][0][c:c + n + L - 1])) < tol, b
+        assert np.max(np.abs(Vd[rows].float().cpu().numpy() - caches[b][1][c:c + n + L - 1])) < tol, b
+
+
+def test_batched_chain_drafting_matches_the_per_sequence_oracle():
+    import paper_2503_01840_amd as E
+    _chain_case(E, S.get_shape("c1"), 3, 3, 3, 1, 1e-4)                     # fp32, exact
+    small = S.get_shape("c2").with_(name="small", hidden=256, n_heads=4, n_kv_heads=2, intermediate=512, vocab=1024,
+                                    draft_vocab=512, n_layers=1, taps=(0, 0, 0))
+    _chain_case(E, small, 5, 1, 2, 2, 2e-2)                                 # one new position per sequence
+    _chain_case(E, small, 7, 4, 3, 3, 2e-2)                                 # ragged n_new, 28 rows in forward 1
+    _chain_case(E, small, 24, 3, 2, 4, 2e-2)                                # 72 rows: the many-row GEMM path

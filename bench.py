@@ -63,6 +63,8 @@ def main():
     torch.cuda.set_device(0)
     if args.config == "c4":
         out = bench_batched(args, shape, torch, S, E, dev)
+        if not args.no_cpu_baseline:
+            out["cpu_baseline"] = cpu_baseline_batched(shape)
         if args.calibrate_copy:
             calibrate_copy(torch, dev)
         print(json.dumps(out))
@@ -121,28 +123,45 @@ def main():
         for i in range(4):
             parts[i] += ev[i].elapsed_time(ev[i + 1]) / reps
 
-    # dominant kernel: the weight-streaming GEMM at verification width (HIP events around every launch)
+    # per-launch kernel durations of the weight-streaming GEMMs (HIP events attached to every dispatch on the stream
+    # in use), by kernel: 64-weight-row workgroups (q/k/v, o, down), 128-weight-row ones (gate/up, LM head), draft GEMMs
     ctx.profile_begin()
     step()
     torch.cuda.synchronize()
-    g_ms, g_n, g_bytes = ctx.profile_read(1)
-    d_ms, d_n, d_bytes = ctx.profile_read(0)
+    t64 = ctx.profile_read(1)
+    t128 = ctx.profile_read(2)
+    few = ctx.profile_read(0)
     ctx.profile_end()
 
+    def kernel_line(name, what, tri):
+        ms, n, by = tri
+        if not n:
+            return None
+        return {"kernel": name, "projections": what, "launches_per_step": n, "avg_launch_us": ms / n * 1e3,
+                "bytes_per_launch": by / n, "achieved": by / ms / 1e6, "unit": "GB/s", "frac": by / ms / 1e6 / HBM_PEAK_GBPS,
+                "ms_per_step": ms}
+
+    kernels = [k for k in (kernel_line("gemm_skinny_kernel<2>", "q/k/v, o, down at 60 activation rows", t64),
+                           kernel_line("gemm_skinny128_kernel", "gate/up, LM head at 60 activation rows", t128),
+                           kernel_line("gemm_skinny_kernel<1>", "every projection of the draft (<= 10 rows), feature fusion", few))
+               if k]
     ab = algorithmic_bytes(shape, n_new)
-    if not g_ms:                 # fp32 tiny configuration: exact-arithmetic kernels, everything sits in L2
+    if not kernels:              # fp32 tiny configuration: exact-arithmetic kernels, everything sits in L2
         roofline = {"bound": "latency", "kernel": "fp32 exact-arithmetic path (tiny configuration)", "achieved": None,
                     "peak": None, "unit": "GB/s", "frac": None, "traffic": None,
                     "step_algorithmic_GB": ab["step"] / 1e9, "step_GBps": ab["step"] / ms_per_step / 1e6}
-    else: roofline = {
-        "bound": "hbm", "kernel": "gemm_skinny_kernel<2> + gemm_skinny128_kernel (the verification GEMMs, 60 activation rows)",
-        "achieved": g_bytes / g_ms / 1e6, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-        "frac": g_bytes / g_ms / 1e6 / HBM_PEAK_GBPS, "traffic": stored_traffic(args.config),
-        "launches_per_step": g_n, "avg_launch_us": g_ms / g_n * 1e3, "bytes_per_launch": g_bytes / g_n,
-        "draft_gemm_GBps": d_bytes / d_ms / 1e6 if d_ms else None,
-        "step_algorithmic_GB": ab["step"] / 1e9, "step_GBps": ab["step"] / ms_per_step / 1e6,
-        "step_frac_of_hbm_peak": ab["step"] / ms_per_step / 1e6 / HBM_PEAK_GBPS,
-    }
+    else:
+        dom = max(kernels, key=lambda k: k["ms_per_step"])          # the kernel with the largest share of the step
+        traffic, traffic_src = stored_traffic(args.config, dom["kernel"])
+        roofline = {
+            "bound": "hbm", "kernel": dom["kernel"] + " (" + dom["projections"] + ")",
+            "achieved": dom["achieved"], "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": dom["frac"],
+            "traffic": traffic, "traffic_source": traffic_src,
+            "launches_per_step": dom["launches_per_step"], "avg_launch_us": dom["avg_launch_us"],
+            "bytes_per_launch": dom["bytes_per_launch"], "kernels": kernels,
+            "step_algorithmic_GB": ab["step"] / 1e9, "step_GBps": ab["step"] / ms_per_step / 1e6,
+            "step_frac_of_hbm_peak": ab["step"] / ms_per_step / 1e6 / HBM_PEAK_GBPS,
+        }
 
     out = {
         "metric": "tree tokens verified/s over the whole draft+verify step (%s-shape bs1)" % ("70B" if args.config == "c5" else "8B"),
@@ -160,7 +179,7 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(shape)
+        out["cpu_baseline"] = cpu_baseline(shape, n_new)
     if args.calibrate_copy:
         calibrate_copy(torch, dev)
     print(json.dumps(out))
@@ -177,17 +196,21 @@ def calibrate_copy(torch, dev):
     torch.cuda.synchronize()
 
 
-def stored_traffic(config):
-    """HBM bytes per launch of the dominant kernel from the committed hardware-counter summary (rocprofv3 --pmc
-    runs of this script are separate invocations: their result is a stored figure, or null)."""
+def stored_traffic(config, kernel):
+    """HBM bytes per launch of `kernel` from the committed hardware-counter summary (rocprofv3 --pmc runs of this
+    script are separate invocations, so the figure is a stored one): (bytes, "file @ commit it was measured at"), or
+    (None, None) when no summary names this kernel."""
     path = os.path.join(ROOT, "profiles", f"{config}_gemm_pmc_traffic.txt")
+    value = commit = None
     try:
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":", 1)[1])
+            if line.startswith(f"traffic_bytes_per_launch[{kernel}]:"):
+                value = float(line.split(":", 1)[1])
+            elif line.startswith("measured_at_commit:"):
+                commit = line.split(":", 1)[1].strip()
     except OSError:
         pass
-    return None
+    return (value, f"profiles/{os.path.basename(path)} @ {commit}") if value is not None else (None, None)
 
 
 def bench_batched(args, shape, torch, S, E, dev):
@@ -230,7 +253,7 @@ def bench_batched(args, shape, torch, S, E, dev):
     ctx.profile_begin()
     step()
     torch.cuda.synchronize()
-    g_ms, g_n, g_bytes = ctx.profile_read(1)
+    g_ms, g_n, g_bytes = ctx.profile_read(3)
     ctx.profile_end()
     R = B * N
     flops = g_bytes * R                      # 2 N K bytes per launch -> 2 R N K FLOP
@@ -255,39 +278,105 @@ def bench_batched(args, shape, torch, S, E, dev):
     }
 
 
-def cpu_baseline(shape, n_layers=8, min_seconds=8.0, max_passes=24):
-    """The oracle as it stands, timed on this machine's host cores over a bounded sample of the same workload:
-    `n_layers` target layers of the tree verification (weights generated beforehand, not timed), repeated until
-    about `min_seconds` of CPU work have been timed."""
-    n_layers = min(n_layers, shape.n_layers)
-    import numpy as np
-    import eagle3_synth as S
-    from oracle import eagle3_oracle as O
+def _threads():
     try:
         from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        return max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
-        cores = os.cpu_count()
-    N, P = shape.n_nodes, shape.prefix_lo
-    parent, _ = S.random_tree(S.SEED, 0, N, shape.depth, shape.topk)
-    tok = S.uniform_ints(S.SEED, S.TensorIds.TREE_TOK, (N,), 0, shape.vocab).numpy()
+        return os.cpu_count()
+
+
+def cpu_baseline(shape, n_new, n_layers=8):
+    """The oracle as it stands, timed on this machine's host cores on the SAME unit as `value` (one whole step: feature
+    fusion, draft expansion, tree verification with the LM head, greedy and T=1 acceptance), over a bounded sample:
+    everything in full except the target stack, of which `n_layers` layers are timed and scaled to all of them.
+    Weights are generated beforehand (not timed)."""
+    import numpy as np
+    import torch
+    import eagle3_synth as S
+    from oracle import eagle3_oracle as O
+    import pipeline as PL
+    n_layers = min(n_layers, shape.n_layers)
+    N, P, D, K = shape.n_nodes, shape.prefix_lo, shape.depth, shape.topk
+    rnd = "bf16" if shape.dtype == "bf16" else "none"
+    lazy = shape.vocab * shape.hidden > 5e8
+    model = PL.OracleModel(shape, cache_layers=False, lazy_embed=lazy)
+    if shape.dtype == "fp32":
+        inp = PL.real_prefill_inputs(shape, model)
+    else:
+        inp = PL.synthetic_step_inputs(shape, n_new=n_new)
+    dw = model.draft()
+    taps = S.normal(S.SEED, S.TensorIds.TAPS, (3, n_new, shape.hidden))
     Ws = [O.weights_f64(S.layer_weights(shape, l)) for l in range(n_layers)]
-    kvs = [tuple(O.as_f64(t) for t in S.kv_layer(shape, l, P)) for l in range(n_layers)]
-    emb = O.as_f64(S.normal(S.SEED, S.TensorIds.EMBED, (shape.vocab, shape.hidden), 0.02, 0.0,
-                            __import__("torch").bfloat16 if shape.dtype == "bf16" else __import__("torch").float32))
+    kvs = [tuple(O.as_f64(t) for t in PL.target_kv_cpu(shape, inp, l)) for l in range(n_layers)]
+    dt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    lm = O.as_f64(S.normal(S.SEED, S.TensorIds.LM_HEAD, (shape.vocab, shape.hidden), 0.02, 0.0, dt))
+    fn = O.as_f64(S.normal(S.SEED, S.TensorIds.FINAL_NORM, (shape.hidden,), 0.02, 1.0, dt))
+    U = S.uniform01(S.SEED, S.TensorIds.UNIFORMS, (2 * N,)).double().numpy()
     sub = shape.with_(n_layers=n_layers, taps=(0, 0, 0))
+    t = {}
     t0 = time.perf_counter()
-    passes = 0
-    while passes < max_passes and (passes == 0 or time.perf_counter() - t0 < min_seconds):
-        O.tree_verify(sub, lambda l: Ws[l], {"embed": emb, "lm_head": None}, tok, parent, lambda l: kvs[l],
-                      rounding="bf16" if shape.dtype == "bf16" else "none")
-        passes += 1
-    dt = (time.perf_counter() - t0) / passes
-    est_verify_s = dt / n_layers * shape.n_layers
-    return {"value": N / est_verify_s, "unit": "tree tokens verified/s", "cores": cores, "kind": "oracle",
-            "sample": f"{n_layers} of {shape.n_layers} target layers of the {N}-node tree verification against a "
-                      f"{P}-token cache, fp64 NumPy, {passes} passes of {dt:.2f} s each, scaled to {shape.n_layers} layers "
-                      "(LM head and draft not included)"}
+    O.fuse_features(dw["w_fc"], *[O.as_f64(taps[i]) for i in range(3)], rounding=rnd)
+    t["fuse"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    tree = PL.oracle_draft(shape, model, inp, D, K, N)
+    t["draft"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    x0 = model.embed()[np.asarray(tree["tree_tok"])]
+    ver = O.tree_verify(sub, lambda l: Ws[l], {"lm_head": None}, tree["tree_tok"], tree["parent"], lambda l: kvs[l],
+                        rounding=rnd, x0=x0)
+    t["verify_layers_sample"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    rd = O._rounder(rnd)
+    logits = rd(O.rmsnorm(ver["x_final"], fn, shape.rms_eps)) @ lm.T
+    t["lm_head"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    O.accept_greedy(logits, tree["tree_tok"], tree["parent"])
+    O.accept_stochastic(logits, tree["tree_tok"], tree["parent"], 1.0, U)
+    t["accept"] = time.perf_counter() - t0
+    step_s = t["fuse"] + t["draft"] + t["verify_layers_sample"] / n_layers * shape.n_layers + t["lm_head"] + t["accept"]
+    return {"value": N / step_s, "unit": "tree tokens verified/s", "cores": _threads(), "kind": "oracle",
+            "step_s_estimated": step_s, "timed_s": {k: round(v, 3) for k, v in t.items()},
+            "sample": f"one whole step of the same workload through the fp64 NumPy oracle: fusion, draft expansion (depth {D}), "
+                      f"LM head and both acceptance walks in full; {n_layers} of the {shape.n_layers} target layers timed and "
+                      f"scaled to {shape.n_layers}"}
+
+
+def cpu_baseline_batched(shape, n_seq=2, n_layers=2):
+    """The oracle on the batched workload's unit (verification + acceptance of every sequence): `n_seq` sequences
+    through `n_layers` target layers plus LM head and acceptance, scaled to the batch and to all layers."""
+    import numpy as np
+    import torch
+    import eagle3_synth as S
+    from oracle import eagle3_oracle as O
+    rb = S.ragged_batch(shape)
+    N = shape.n_nodes
+    Ws = [O.weights_f64(S.layer_weights(shape, l)) for l in range(n_layers)]
+    lm = O.as_f64(S.normal(S.SEED, S.TensorIds.LM_HEAD, (shape.vocab, shape.hidden), 0.02, 0.0, torch.bfloat16))
+    fn = O.as_f64(S.normal(S.SEED, S.TensorIds.FINAL_NORM, (shape.hidden,), 0.02, 1.0, torch.bfloat16))
+    import pipeline as PL
+    emb = PL.LazyEmbedRows(shape)
+    sub = shape.with_(n_layers=n_layers, taps=(0, 0, 0))
+    rd = O._rounder("bf16")
+    t_layers = t_rest = 0.0
+    for b in range(n_seq):
+        P, base = int(rb["prefix_len"][b]), int(rb["kv_indptr"][b])
+        kvs = [tuple(O.as_f64(t) for t in S.kv_layer(shape, l, P, first_slot=base)) for l in range(n_layers)]
+        U = S.uniform01(S.SEED + b, S.TensorIds.UNIFORMS, (2 * N,)).double().numpy()
+        t0 = time.perf_counter()
+        ver = O.tree_verify(sub, lambda l: Ws[l], {"lm_head": None}, rb["tree_tok"][b], rb["parent"][b],
+                            lambda l: kvs[l], rounding="bf16", x0=emb[np.asarray(rb["tree_tok"][b])])
+        t_layers += time.perf_counter() - t0
+        t0 = time.perf_counter()
+        logits = rd(O.rmsnorm(ver["x_final"], fn, shape.rms_eps)) @ lm.T
+        O.accept_greedy(logits, rb["tree_tok"][b], rb["parent"][b])
+        O.accept_stochastic(logits, rb["tree_tok"][b], rb["parent"][b], 1.0, U)
+        t_rest += time.perf_counter() - t0
+    step_s = (t_layers / n_layers * shape.n_layers + t_rest) / n_seq * shape.batch
+    return {"value": shape.batch * N / step_s, "unit": "tree tokens verified/s", "cores": _threads(), "kind": "oracle",
+            "step_s_estimated": step_s,
+            "sample": f"{n_seq} of the {shape.batch} sequences through {n_layers} of the {shape.n_layers} target layers, LM head and "
+                      f"both acceptance walks in full (fp64 NumPy oracle), scaled to the batch and to {shape.n_layers} layers"}
 
 
 if __name__ == "__main__":

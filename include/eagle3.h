@@ -111,17 +111,6 @@ int eagle3_set_weights(eagle3_ctx* ctx, const eagle3_target_weights* target /* m
 const char* eagle3_strerror(int code);
 const char* eagle3_last_error(void);      /* text of the last HIP failure seen by this thread */
 
-/* ---- measurement aid (host only) -----------------------------------------------------------------
- * While profiling is on, every weight-streaming GEMM launch of the step calls carries a start/stop pair of
- * HIP events attached to the dispatch itself on the caller's stream, i.e. the kernel's own begin and end
- * timestamps (the launches no longer overlap their neighbours: do not time whole steps with it on).
- * eagle3_profile_read synchronises, then reports the summed kernel duration, the number of launches and the
- * weight bytes those launches read, for launches with more than 32 activation rows (`wide` != 0: the
- * verification GEMMs) or with at most 32 (`wide` == 0: the draft GEMMs), and resets the counters. */
-int eagle3_profile_begin(eagle3_ctx* ctx);
-int eagle3_profile_read(eagle3_ctx* ctx, int wide, double* ms_total, int64_t* launches, double* weight_bytes);
-int eagle3_profile_end(eagle3_ctx* ctx);
-
 /* ---- the speculative step ---------------------------------------------------------------------- */
 
 /* Section 3.1 ("Inference Pipeline"): the k-dimensional low, mid and high features of a position are

@@ -199,10 +199,12 @@ class Eagle3Context:
     def profile_begin(self):
         _check(lib().eagle3_profile_begin(self._h))
 
-    def profile_read(self, wide):
-        """(total ms, launches, weight bytes) of the GEMM launches since the last read; wide = verify-sized."""
+    def profile_read(self, kind):
+        """(total ms, launches, weight bytes) of the GEMM launches of one kind since profile_begin: 0 = at most 32
+        rows, 1 = 33..64 rows with 64-weight-row workgroups, 2 = 33..64 rows with 128-weight-row workgroups,
+        3 = more than 64 rows (see include/eagle3_measure.h)."""
         ms, n, by = C.c_double(), C.c_int64(), C.c_double()
-        _check(lib().eagle3_profile_read(self._h, int(bool(wide)), C.byref(ms), C.byref(n), C.byref(by)))
+        _check(lib().eagle3_profile_read(self._h, int(kind), C.byref(ms), C.byref(n), C.byref(by)))
         return ms.value, n.value, by.value
 
     def profile_end(self):

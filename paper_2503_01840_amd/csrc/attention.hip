@@ -202,14 +202,16 @@ __global__ __launch_bounds__(128 * CW, CW == 1 ? 1 : 2) void attn_tree_bf16_kern
     }
     const int kb = t * KT + 32 * sb;
     float mx = NEG;
-    if (kb + 32 > si.n_prefix) {                       // uniform per wavefront: the block touches the masked tail or the end
+    const bool masked_block = kb + 32 > si.n_prefix;   // uniform per wavefront: the block touches the masked tail or the end
+    uint32_t vis = 0xFFFFFFFFu;
+    if (masked_block) {
       // visibility of the block's 32 keys as one word per lane: bit i <-> key kb + i
       const int off0 = kb - si.n_prefix, w0 = off0 >> 5, sh = off0 & 31;
       auto word = [&](int i) -> uint32_t {             // i is uniform; keys before the tail are all visible
         return i < 0 ? 0xFFFFFFFFu : i == 0 ? mw[0] : i == 1 ? mw[1] : i == 2 ? mw[2] : i == 3 ? mw[3] : 0u;
       };
       const uint64_t both = ((uint64_t)word(w0 + 1) << 32) | word(w0);
-      uint32_t vis = (uint32_t)(both >> sh);
+      vis = (uint32_t)(both >> sh);
       if (L - kb < 32) vis &= L > kb ? (1u << (L - kb)) - 1u : 0u;       // keys past the end of the sequence
       vis >>= 4 * kg;
 #pragma unroll
@@ -232,10 +234,21 @@ __global__ __launch_bounds__(128 * CW, CW == 1 ? 1 : 2) void attn_tree_bf16_kern
     const float m_new = __any(m_cand - m_run > MAX_SLACK) ? m_cand : m_run;
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     float ls = 0.f;
+    if (masked_block) {
+      // invisible keys get weight zero by selection, not by the size of NEG: when a wavefront's first blocks are
+      // wholly invisible for a row, m_new itself is NEG-like and the exponent of a masked score is a rounding remainder
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      s[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], p.scale_log2, -m_new));
-      ls += s[r];
+      for (int r = 0; r < 16; ++r) {
+        const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], p.scale_log2, -m_new));
+        s[r] = ((vis >> (8 * (r >> 2) + (r & 3))) & 1u) ? e : 0.f;
+        ls += s[r];
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        s[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], p.scale_log2, -m_new));
+        ls += s[r];
+      }
     }
     pair_values(ls, xa, xb);
     l_run = l_run * alpha + (xa + xb);
@@ -475,12 +488,9 @@ static hipError_t launch_attn_cw(const AttnParams& p, int grid, hipStream_t st) 
   // the tile ring, reused by the end-of-kernel merge of the two key-block halves
   constexpr int LDS = RD * TILE_BYTES > CW * 66 * 64 * 4 ? RD * TILE_BYTES : CW * 66 * 64 * 4;
   auto kernel = attn_tree_bf16_kernel<CW>;
-  static bool configured = false;                // per process; the attribute belongs to the code object
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static DeviceOnce configured;                  // the attribute belongs to the loaded code object of a device
+  hipError_t ce = configured.run([&] { return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS); });
+  if (ce != hipSuccess) return ce;
   hipLaunchKernelGGL(kernel, dim3(grid), dim3(128 * CW), LDS, st, p);
   return hipGetLastError();
 }

@@ -167,6 +167,25 @@ __device__ __forceinline__ float block_max(float v, float* red) {
   return red[16];
 }
 
+// Runs a set-up call once per device (the device current at the call), thread-safe: kernel attributes such as the
+// dynamic-LDS limit belong to the code object loaded on ONE device.
+#include <mutex>
+struct DeviceOnce {
+  std::mutex mu;
+  bool done[64] = {};
+  template <typename F> hipError_t run(F&& f) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (done[dev]) return hipSuccess;
+    e = f();
+    if (e == hipSuccess) done[dev] = true;
+    return e;
+  }
+};
+
 // Launch with an optional start/stop event pair attached to the dispatch itself: the events then carry the
 // kernel's own begin and end timestamps (what a kernel trace reports), not the time between two stream markers.
 template <typename Kernel, typename Params>

@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "../../include/eagle3.h"
+#include "../../include/eagle3_measure.h"
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -55,7 +56,7 @@ struct eagle3_ctx {
 
   // optional per-launch timing of the GEMMs
   bool profiling = false;
-  struct Stamp { hipEvent_t a, b; double bytes; bool wide; };
+  struct Stamp { hipEvent_t a, b; double bytes; int kind; };
   std::vector<Stamp> stamps;
   size_t stamps_used = 0;
 
@@ -129,7 +130,7 @@ struct eagle3_ctx {
               float* direct_out = nullptr) {
     if (bf16 && M > 64) {
       Stamp* sp = profiling && stamps_used < stamps.size() ? &stamps[stamps_used++] : nullptr;
-      if (sp) { sp->bytes = 2.0 * N * K; sp->wide = true; }
+      if (sp) { sp->bytes = 2.0 * N * K; sp->kind = EAGLE3_GEMM_MANY_ROWS; }
       int S = 1;
       void* out = epi == GEMM_EPI_SWIGLU ? act_h : (direct_out ? (void*)direct_out : (void*)part);
       CK(launch_gemm_wide((const bf16_t*)act_in, W, M, N, K, epi, out, direct_out ? 0 : part_floats, &S, st,
@@ -143,7 +144,10 @@ struct eagle3_ctx {
       if (epi == GEMM_EPI_PARTIAL && direct_out == nullptr && (size_t)S * M * N > part_floats) return EAGLE3_E_STATE;
       void* out = epi == GEMM_EPI_SWIGLU ? act_h : (direct_out && S == 1 ? (void*)direct_out : (void*)part);
       Stamp* sp = profiling && stamps_used < stamps.size() ? &stamps[stamps_used++] : nullptr;
-      if (sp) { sp->bytes = 2.0 * N * K; sp->wide = M > 32; }
+      if (sp) {
+        sp->bytes = 2.0 * N * K;
+        sp->kind = M <= 32 ? EAGLE3_GEMM_FEW_ROWS : gemm_skinny_uses_tile128(W, M, N, S) ? EAGLE3_GEMM_TILE128 : EAGLE3_GEMM_TILE64;
+      }
       CK(launch_gemm_skinny((const bf16_t*)act_in, W, M, N, K, S, epi, out, st, sp ? sp->a : nullptr, sp ? sp->b : nullptr));
       if (direct_out && S > 1) CK(launch_reduce_partials(part, S, M, N, direct_out, st));
       if (S_out) *S_out = S;
@@ -295,13 +299,13 @@ int eagle3_profile_begin(eagle3_ctx* ctx) {
   return EAGLE3_OK;
 }
 
-int eagle3_profile_read(eagle3_ctx* ctx, int wide, double* ms_total, int64_t* launches, double* weight_bytes) {
+int eagle3_profile_read(eagle3_ctx* ctx, int kind, double* ms_total, int64_t* launches, double* weight_bytes) {
   if (!ctx || !ms_total || !launches || !weight_bytes) return EAGLE3_E_NULL;
   double ms = 0, bytes = 0;
   int64_t n = 0;
   for (size_t i = 0; i < ctx->stamps_used; ++i) {
     auto& s = ctx->stamps[i];
-    if (s.wide != (wide != 0)) continue;
+    if (s.kind != kind) continue;
     CK(hipEventSynchronize(s.b));
     float t = 0.f;
     CK(hipEventElapsedTime(&t, s.a, s.b));

@@ -373,6 +373,11 @@ int gemm_skinny_pick_splits(int N, int K, int M) {
   return best;
 }
 
+bool gemm_skinny_uses_tile128(const GemmWeights& W, int M, int N, int S) {
+  const int tiles128 = W.mode == 1 ? (N / 2 + 63) / 64 : (N + wide_tile::BN2 - 1) / wide_tile::BN2;
+  return M > 32 && S == 1 && tiles128 >= 192;
+}
+
 hipError_t launch_gemm_skinny(const bf16_t* x, const GemmWeights& W, int M, int N, int K, int S, int epi, void* out,
                               hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (M <= 0 || N <= 0 || K <= 0 || S <= 0 || K % (BK * S) != 0) return hipErrorInvalidValue;
@@ -386,16 +391,13 @@ hipError_t launch_gemm_skinny(const bf16_t* x, const GemmWeights& W, int M, int 
   // 33..64 rows: 128 weight rows per workgroup where that still gives most CUs a tile without split-K (gate/up,
   // LM head: 5 % faster); matrices with few rows need the splits for parallelism and then the smaller
   // workgroup's shorter prologue and reduction win (q/k/v, o, down: 5-15 % slower with the large tile)
-  const int tiles128 = W.mode == 1 ? (N / 2 + 63) / 64 : (N + wide_tile::BN2 - 1) / wide_tile::BN2;
-  if (M > 32 && S == 1 && tiles128 >= 192) {
-    const int tiles = tiles128;
-    static bool configured = false;              // per process; the attribute belongs to the code object
-    if (!configured) {
-      hipError_t e = hipFuncSetAttribute((const void*)gemm_skinny128_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         wide_tile::SMEM2);
-      if (e != hipSuccess) return e;
-      configured = true;
-    }
+  if (gemm_skinny_uses_tile128(W, M, N, S)) {
+    const int tiles = W.mode == 1 ? (N / 2 + 63) / 64 : (N + wide_tile::BN2 - 1) / wide_tile::BN2;
+    static DeviceOnce configured;                // the attribute belongs to the loaded code object of a device
+    hipError_t ce = configured.run([&] {
+      return hipFuncSetAttribute((const void*)gemm_skinny128_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, wide_tile::SMEM2);
+    });
+    if (ce != hipSuccess) return ce;
     launch_with_events(gemm_skinny128_kernel, dim3(tiles, S, (M + 63) / 64), dim3(512), wide_tile::SMEM2, st, ev_start, ev_stop, p);
     return hipGetLastError();
   }

@@ -235,12 +235,9 @@ hipError_t launch_cfg(WideParams& p, int S, hipStream_t st, hipEvent_t ev_start,
   constexpr int TM = 32 * FM * WGM, TN = 32 * FN * WGN;
   constexpr int LDS = A_SLOTS * TM * (BK / 2) * 2 + B_SLOTS * TN * BK * 2;
   auto kernel = gemm_wide_kernel<WGM, WGN, FM, FN, OCC>;
-  static bool configured = false;                      // per process; the attribute belongs to the code object
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static DeviceOnce configured;                        // the attribute belongs to the loaded code object of a device
+  hipError_t ce = configured.run([&] { return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS); });
+  if (ce != hipSuccess) return ce;
   p.tiles = (p.N + TN - 1) / TN;
   p.groups = (p.tiles + 7) / 8;
   p.mblocks = (p.M + TM - 1) / TM;

@@ -25,6 +25,8 @@ enum { GEMM_EPI_PARTIAL = 0, GEMM_EPI_SWIGLU = 1 };
 // Requires K % (128*S) == 0.  N = total weight rows.  ev_start / ev_stop (optional): events attached to the dispatch.
 hipError_t launch_gemm_skinny(const bf16_t* x, const GemmWeights& W, int M, int N, int K, int S, int epi,
                               void* out, hipStream_t st, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+// Whether launch_gemm_skinny takes the 128-weight-row workgroups for this shape.
+bool gemm_skinny_uses_tile128(const GemmWeights& W, int M, int N, int S);
 // Chooses the split-K factor for a [N, K] weight so that about two workgroups per CU are resident.
 int gemm_skinny_pick_splits(int N, int K, int M);
 

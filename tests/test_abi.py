@@ -21,7 +21,7 @@ def L():
 
 
 def test_every_symbol_declared_in_the_header_is_exported(L):
-    header = open(os.path.join(ROOT, "include", "eagle3.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("eagle3.h", "eagle3_measure.h"))
     declared = set(re.findall(r"\b(eagle3_[a-z_]+)\s*\(", header))
     assert declared == set(E.EXPORTS)
     for name in declared:

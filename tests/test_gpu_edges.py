@@ -63,6 +63,8 @@ def test_verify_degenerate_trees_and_prefixes(shape):
         (S.chain_tree(16)[0], 0),                             # empty prefix: the tree is the whole context
         (np.array([-1], dtype=np.int32), 0),                  # one token, nothing cached
         (star, 31),                                           # star: every node sees only the root and itself
+        (np.array([-1] + [0] * 39, dtype=np.int32), 0),       # star of 40 without a prefix: for the first 32 rows the
+                                                              # second 32-key block of the only tile is wholly invisible
         (S.chain_tree(64)[0], 65),                            # maximum node count as one deep chain
         (S.random_tree(S.SEED, 9, 64, 6, 10)[0], 97),         # maximum node count, bushy; prefix not a tile multiple
         (S.random_tree(S.SEED, 10, 33, 5, 4)[0], 1),          # one cached token; node count just past a 32-tile

@@ -165,6 +165,32 @@ def attention_explicit_sets(q, K, V, visible_slots):
     return out
 
 
+def ttt_visible_sets(T, s):
+    """Training-time test, simulated step s (Section 3.2, Figure 6; s = 0 is the native step): query i of step s sees
+    the ORIGINAL training positions 0..i (ordinary causal context) and, of every simulated step t = 1..s, only
+    position i itself (those masks are diagonal).  Keys are numbered t * T + j.  Returns the list of visible key
+    numbers per query."""
+    return [list(range(i + 1)) + [t * T + i for t in range(1, s + 1)] for i in range(T)]
+
+
+def ttt_attention(q, K_steps, V_steps, form="sets"):
+    """Self-attention of the draft layer during a training-time-test step (Section 3.2).  q [T,H,d] = the queries of
+    step s; K_steps, V_steps [s+1, T, Hkv, d] = keys / values of the original inputs (index 0) and of the simulated
+    steps 1..s (index s = this step's own).  form "sets": every query runs plain softmax attention over exactly its
+    visible keys; form "mask": one dense masked attention over all (s+1) T keys.  Returns [T,H,d]."""
+    n_steps, T = K_steps.shape[0], K_steps.shape[1]
+    s = n_steps - 1
+    K = K_steps.reshape(n_steps * T, *K_steps.shape[2:])
+    V = V_steps.reshape(n_steps * T, *V_steps.shape[2:])
+    sets = ttt_visible_sets(T, s)
+    if form == "sets":
+        return attention_explicit_sets(q, K, V, sets)
+    vis = np.zeros((T, n_steps * T), dtype=bool)
+    for i, idx in enumerate(sets):
+        vis[i, idx] = True
+    return attention_prefix_tail(q, K, V, 0, vis)
+
+
 # ----------------------------------------------------------------------------- target model
 
 def _mlp(n2, W, rd):

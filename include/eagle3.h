@@ -235,6 +235,19 @@ int eagle3_commit(eagle3_ctx* ctx, int32_t B, int32_t N, const int32_t* tree_tok
                   const float* taps, int32_t rows, float* taps_new, int32_t* tok_new, int32_t* n_new,
                   int32_t* draft_prefix_len, int32_t draft_rows, eagle3_stream stream);
 
+/* Section 3.2 ("Draft Model Training", Figure 6), forward only: the draft layer's self-attention during a
+ * training-time-test step.  At simulated step `step` (0 = the native step) query i attends to the ORIGINAL
+ * training positions 0..i (a lower-triangular mask) and, of every simulated step t = 1..step, to position i alone
+ * (diagonal masks; those scores are per-position vector dot products, not a matrix product).  No context needed.
+ *   dtype    EAGLE3_BF16 (head_dim must be 128) or EAGLE3_FP32 (exact kernels, (T + step) * 4 bytes <= 60 KiB)
+ *   q        [T, n_heads, head_dim]                 queries of this step (already rotated)
+ *   k_steps  [step + 1, T, n_kv_heads, head_dim]    keys of the original inputs (index 0) and of steps 1..step
+ *   v_steps  [step + 1, T, n_kv_heads, head_dim]    values, same order
+ *   out      fp32 [T, n_heads, head_dim]
+ * Softmax scale 1/sqrt(head_dim); query head h reads KV head h * n_kv_heads / n_heads. */
+int eagle3_ttt_attention(int32_t dtype, int32_t T, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, int32_t step,
+                         const void* q, const void* k_steps, const void* v_steps, float* out, eagle3_stream stream);
+
 /* For callers that cannot allocate device memory and hold no context: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  The same acceptance walk as eagle3_accept (same kernels, same
  * results) with its per-(row, 2048-logit chunk) statistics kept in a fixed 1 MiB device array inside the library

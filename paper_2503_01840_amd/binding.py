@@ -17,7 +17,7 @@ EAGLE3_FP32, EAGLE3_BF16 = 0, 1
 EXPORTS = ["eagle3_create", "eagle3_destroy", "eagle3_workspace_bytes", "eagle3_set_workspace", "eagle3_set_weights",
            "eagle3_strerror", "eagle3_last_error", "eagle3_profile_begin", "eagle3_profile_read", "eagle3_profile_end",
            "eagle3_fuse_features", "eagle3_draft_expand",
-           "eagle3_tree_verify", "eagle3_tree_verify_layers", "eagle3_accept", "eagle3_accept_static", "eagle3_commit", "eagle3_prefill", "eagle3_draft_chain"]
+           "eagle3_tree_verify", "eagle3_tree_verify_layers", "eagle3_accept", "eagle3_accept_static", "eagle3_commit", "eagle3_prefill", "eagle3_draft_chain", "eagle3_ttt_attention"]
 
 
 class Config(C.Structure):
@@ -92,6 +92,7 @@ def lib():
                                      C.c_void_p]
         L.eagle3_draft_chain.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(KV),
                                          C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.eagle3_ttt_attention.argtypes = [C.c_int32] * 6 + [C.c_void_p] * 5
         _lib = L
     return _lib
 
@@ -358,3 +359,14 @@ def eagle3_draft_chain(ctx, g_new, tok_new, n_new, draft_kv, length):
                                     _ptr(n_new, torch.int32), rows1, C.byref(draft_kv.c), int(length), _ptr(chain_tok),
                                     _ptr(chain_logp), _stream()))
     return chain_tok, chain_logp
+
+
+def eagle3_ttt_attention(q, k_steps, v_steps):
+    """Training-time-test attention forward.  q [T,H,d], k_steps / v_steps [s+1,T,Hkv,d] (bf16 or fp32) -> fp32 [T,H,d]."""
+    T, H, d = q.shape
+    s, Hkv = k_steps.shape[0] - 1, k_steps.shape[2]
+    dt = EAGLE3_BF16 if q.dtype == torch.bfloat16 else EAGLE3_FP32
+    out = torch.empty(T, H, d, dtype=torch.float32, device=q.device)
+    _check(lib().eagle3_ttt_attention(dt, T, H, Hkv, d, s, _ptr(q), _ptr(k_steps, q.dtype), _ptr(v_steps, q.dtype), _ptr(out),
+                                      _stream()))
+    return out

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libeagle3.so")
 SOURCES = ["eagle3_api.hip", "gemm_skinny.hip", "gemm_wide.hip", "gemm_f32.hip", "elementwise.hip", "attention.hip", "select.hip",
-           "accept.hip", "commit.hip"]
+           "accept.hip", "commit.hip", "ttt_attention.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

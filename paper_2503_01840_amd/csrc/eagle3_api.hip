@@ -630,6 +630,17 @@ int eagle3_prefill(eagle3_ctx* ctx, const int32_t* tokens, int32_t T, const eagl
   return EAGLE3_OK;
 }
 
+int eagle3_ttt_attention(int32_t dtype, int32_t T, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, int32_t step,
+                         const void* q, const void* k_steps, const void* v_steps, float* out, eagle3_stream stream) {
+  if (!q || !k_steps || !v_steps || !out) return EAGLE3_E_NULL;
+  if (dtype != EAGLE3_BF16 && dtype != EAGLE3_FP32) return EAGLE3_E_SHAPE;
+  if (T < 1 || n_heads < 1 || n_kv_heads < 1 || n_heads % n_kv_heads || step < 0 || head_dim < 1) return EAGLE3_E_SHAPE;
+  if (dtype == EAGLE3_BF16 ? head_dim != 128 : (head_dim > 1024 || (size_t)(T + step) * 4 > 60 * 1024)) return EAGLE3_E_SHAPE;
+  CK(launch_ttt_attention(dtype == EAGLE3_BF16, q, k_steps, v_steps, T, n_heads, n_kv_heads, head_dim, step, out,
+                          (hipStream_t)stream));
+  return EAGLE3_OK;
+}
+
 int eagle3_commit(eagle3_ctx* ctx, int32_t B, int32_t N, const int32_t* tree_tok, const int32_t* path,
                   const int32_t* accept_len, const int32_t* bonus_tok, const eagle3_kv* kv, int32_t* prefix_len,
                   const float* taps, int32_t rows, float* taps_new, int32_t* tok_new, int32_t* n_new,

@@ -152,3 +152,8 @@ hipError_t launch_commit(void* const* k_layers, void* const* v_layers, int n_lay
                          const int32_t* bonus, const float* taps, int B, int N, int hidden, int row_bytes, int rows,
                          float* taps_new, int32_t* tok_new, int32_t* n_new, int32_t* draft_prefix_len, int draft_rows,
                          hipStream_t st);
+
+// ---------------------------------------------------------------- training-time-test attention (ttt_attention.hip)
+// q [T,H,d], k / v [s+1,T,Hkv,d] (bf16 with d == 128, or fp32), out fp32 [T,H,d].
+hipError_t launch_ttt_attention(bool bf16, const void* q, const void* k, const void* v, int T, int H, int Hkv, int d, int s,
+                                float* out, hipStream_t st);

@@ -45,7 +45,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c4", "c5", "chain", "ttt"])
     ap.add_argument("--calibrate-copy", action="store_true")
     ap.add_argument("--n-new", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -58,9 +58,15 @@ def main():
     import eagle3_synth as S
     import paper_2503_01840_amd as E
 
-    shape = S.get_shape(args.config)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.config == "chain":
+        print(json.dumps(bench_chain(args, S.get_shape("c4"), torch, S, E, dev)))
+        return
+    if args.config == "ttt":
+        print(json.dumps(bench_ttt(args, torch, S, E, dev)))
+        return
+    shape = S.get_shape(args.config)
     if args.config == "c4":
         out = bench_batched(args, shape, torch, S, E, dev)
         if not args.no_cpu_baseline:
@@ -276,6 +282,94 @@ def bench_batched(args, shape, torch, S, E, dev):
             "kv_cache_GB_per_step": kv_bytes / 1e9, "weights_GB_per_step": g_bytes / 1e9,
         },
     }
+
+
+def bench_chain(args, shape, torch, S, E, dev, length=3):
+    """The serving regime of Sections 4.3 / 4.4 at the batch-64 shape: per step one batched chain draft (3 tokens per
+    sequence, no tree), verification of the 64 four-node chains through the 32 target layers, acceptance, commit."""
+    rb = S.ragged_batch(shape)
+    B, N = shape.batch, length + 1
+    ctx = E.Eagle3Context(shape, max_batch=B, max_nodes=8, max_depth=4, max_topk=2, max_new=8, device=dev)
+    tg = S.target_globals(shape, device=dev)
+    ctx.set_weights({"layers": [S.layer_weights(shape, l, device=dev) for l in range(shape.n_layers)], **tg},
+                    S.draft_weights(shape, device=dev))
+    plen = rb["prefix_len"].astype("int64")
+    import numpy as np
+    indptr = np.zeros(B + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum(plen + 8)
+    total = int(indptr[-1])
+    ks, vs = zip(*[S.kv_layer(shape, l, total, device=dev) for l in range(shape.n_layers)])
+    i32 = lambda a: torch.as_tensor(np.asarray(a), dtype=torch.int32, device=dev)
+    plen0 = i32(plen)
+    kv = E.KVCache(ks, vs, i32(indptr), plen0.clone(), int(plen.max()))
+    dk, dv = S.kv_layer(shape, 0, total, device=dev, draft=True)
+    dkv = E.KVCache([dk], [dv], i32(indptr), plen0.clone(), int(plen.max()))
+    g = S.normal(S.SEED, S.TensorIds.G_NEW, (B, 1, shape.hidden), device=dev)
+    tok = S.uniform_ints(S.SEED, S.TensorIds.TOK_NEW, (B, 1), 0, shape.vocab, device=dev)
+    n_new = torch.ones(B, dtype=torch.int32, device=dev)
+    parent = i32(np.tile(np.arange(-1, length), (B, 1)))
+    logits = torch.empty(B, N, shape.vocab, device=dev)
+    taps = torch.empty(3, B, N, shape.hidden, device=dev)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+
+    def step(record=False):
+        if record: ev[0].record()
+        chain_tok, _ = E.eagle3_draft_chain(ctx, g, tok, n_new, dkv, length)
+        if record: ev[1].record()
+        E.eagle3_tree_verify(ctx, chain_tok, parent, kv, logits=logits, taps=taps)
+        if record: ev[2].record()
+        al, path, bonus = E.eagle3_accept(ctx, logits, chain_tok, parent, 0.0)
+        E.eagle3_commit(ctx, chain_tok, path, al, bonus, kv, taps, N, draft_kv=dkv, draft_rows=1)
+        if record: ev[3].record()
+        kv.prefix_len.copy_(plen0)                       # the same workload every step
+        dkv.prefix_len.copy_(plen0)
+
+    steps = min(args.steps, 10)
+    for _ in range(min(args.warmup, 3)):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / steps * 1e3
+    step(record=True)
+    torch.cuda.synchronize()
+    parts = [ev[i].elapsed_time(ev[i + 1]) for i in range(3)]
+    return {
+        "metric": "chain tokens verified/s over batched chain draft + verification + acceptance + commit (8B-shape bs64)",
+        "value": B * N / ms_per_step * 1e3, "unit": "tree tokens verified/s", "n_gpus": 1, "steps": steps,
+        "warmup": min(args.warmup, 3), "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"chain: {B} sequences, ragged caches of {int(plen.min())}..{int(plen.max())} tokens, chains of "
+                               f"{length} draft tokens (no tree), {shape.n_layers}-layer LLaMA-8B-shaped target", "parallelism": "single GPU"},
+        "call_us": {"draft_chain": parts[0] * 1e3, "tree_verify": parts[1] * 1e3, "accept_plus_commit": parts[2] * 1e3},
+    }
+
+
+def bench_ttt(args, torch, S, E, dev, T=2048, H=32, Hkv=8, d=128, s=2):
+    """Training-time-test attention forward at an 8B-shaped training size: 2048 positions, third step."""
+    q = S.normal(S.SEED, 1, (T, H, d), dtype=torch.bfloat16, device=dev)
+    k = S.normal(S.SEED, 2, (s + 1, T, Hkv, d), dtype=torch.bfloat16, device=dev)
+    v = S.normal(S.SEED, 3, (s + 1, T, Hkv, d), dtype=torch.bfloat16, device=dev)
+    for _ in range(3):
+        E.eagle3_ttt_attention(q, k, v)
+    torch.cuda.synchronize()
+    reps = 50
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        E.eagle3_ttt_attention(q, k, v)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / reps * 1e3
+    pairs = T * (T + 1) / 2 + s * T                      # visible (query, key) pairs per head
+    flops = 4.0 * pairs * d * H                          # scores + values, what the method needs
+    return {"metric": "training-time-test attention forward", "value": ms * 1e3, "unit": "us per call", "n_gpus": 1,
+            "higher_is_better": False, "dtype": "bf16", "data": "synthetic", "ms_per_step": ms,
+            "config": {"workload": f"ttt: T={T}, {H} heads / {Hkv} KV heads x {d}, simulated step {s}"},
+            "roofline": {"bound": "mfma", "achieved": flops / ms / 1e9, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": flops / ms / 1e9 / MFMA_PEAK_TFLOPS, "traffic": None,
+                         "note": "algorithmic FLOP of the visible pairs only; the kernel also spends MFMAs on the bf16 tail of exp(S) "
+                                 "and on the masked half of the diagonal tiles"}}
 
 
 def _threads():

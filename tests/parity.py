@@ -24,8 +24,9 @@ def rms(a):
 
 
 def draft_tolerances(g, depth):
-    """(near-tie margin, allowed score error per level) from the oracle's stored self-drift of the scores."""
-    per_level = np.maximum(1e-2, RMS_FACTOR * np.asarray(g["draft_drift_all_per_level"], dtype=np.float64))
+    """(near-tie margin, allowed score error per level) from the oracle's stored self-drift of the scores: the
+    per-level figures are maxima over a level's candidates, so the factor for maxima applies."""
+    per_level = np.maximum(1e-2, MAX_FACTOR * np.asarray(g["draft_drift_all_per_level"], dtype=np.float64))
     assert len(per_level) == depth
     return float(max(1e-2, np.max(g["draft_drift_all_per_level"]))), per_level
 

@@ -12,7 +12,7 @@ for the logits,
     RMS(GPU - oracle) <= 1.5 * RMS drift_all      and      max|GPU - oracle| <= 2 * max drift_all
 (never tighter than the single-layer tolerance), identical arg-max wherever the oracle's top-1 margin exceeds the max
 bound, and they print the measured figures (collected in profiles/parity_errors.txt).  The draft's cumulative scores
-and near-tie margin are bounded the same way by the stored per-level score drift.
+and near-tie margin are bounded the same way by the stored per-level score drift (maxima: factor 2).
 
 c2 (one 8B-shaped layer + LM head, draft depth 6) runs the oracle online.  c3 / c4 / c5 compare with the stored
 oracle outputs: residual stream after selected layers and the taps in full (every row and column), logits at 2048

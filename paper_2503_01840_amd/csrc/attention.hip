@@ -91,7 +91,7 @@ __global__ __launch_bounds__(128 * CW, CW == 1 ? 1 : 2) void attn_tree_bf16_kern
   const int g = idx % p.Hkv; idx /= p.Hkv;
   const int split = idx % p.n_splits; idx /= p.n_splits;
   const int qb = idx % p.n_qblocks;
-  const int b = p.seq[idx / p.n_qblocks].order;      // longest sequences first
+  const int b = p.B == 1 ? 0 : p.seq[idx / p.n_qblocks].order;      // longest sequences first (one sequence: no look-up)
   const int G = p.H / p.Hkv, N = p.N;
   const SeqInfo si = p.seq[b];
   const int L = si.n_prefix + si.n_tail;

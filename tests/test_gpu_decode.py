@@ -239,3 +239,73 @@ def test_batched_chain_drafting_matches_the_per_sequence_oracle():
     _chain_case(E, small, 5, 1, 2, 2, 2e-2)                                 # one new position per sequence
     _chain_case(E, small, 7, 4, 3, 3, 2e-2)                                 # ragged n_new, 28 rows in forward 1
     _chain_case(E, small, 24, 3, 2, 4, 2e-2)                                # 72 rows: the many-row GEMM path
+
+
+def test_batched_chain_decoding_equals_plain_greedy_decoding_per_sequence():
+    """The serving regime of Sections 4.3 / 4.4 end to end on the tiny model: three sequences with different prompts
+    share one ragged cache; per cycle one batched chain draft (3 tokens), one batched verification of the 4-node chains,
+    acceptance and commit for the whole batch; the next cycle's rows per sequence are ragged (accept_len + 1).  Every
+    sequence must reproduce its own plain greedy decoding; planted continuations exercise every accepted length."""
+    import paper_2503_01840_amd as E
+    shape = S.get_shape("c1")
+    model = PL.OracleModel(shape)
+    B, L, n_steps = 3, 3, 8
+    N = L + 1
+    lens = [9, 17, 12]
+    prompts = [S.uniform_ints(S.SEED + 40 + b, S.TensorIds.PREFIX_TOK, (lens[b],), 0, shape.vocab).numpy() for b in range(B)]
+    refs = [O.greedy_decode(shape, model.layer, model.globals(), prompts[b], 40) for b in range(B)]
+    ctx = E.Eagle3Context(shape, max_batch=B, max_nodes=32, max_depth=4, max_topk=4, max_new=32, device=DEV)
+    W = PL.device_weights(shape, device=DEV)
+    ctx.set_weights(W["target"], W["draft"])
+    cap = max(lens) + n_steps * N + 16
+    i32 = lambda v: torch.tensor(v, dtype=torch.int32, device=DEV)
+    z = lambda: torch.zeros(B * cap, shape.n_kv_heads, shape.head_dim, dtype=torch.float32, device=DEV)
+    ks, vs = [z() for _ in range(shape.n_layers)], [z() for _ in range(shape.n_layers)]
+    dk, dv = z(), z()
+    indptr = i32([b * cap for b in range(B + 1)])
+    plen, dplen = i32([0] * B), i32([0] * B)
+    kv = E.KVCache(ks, vs, indptr, plen, 0)
+    dkv = E.KVCache([dk], [dv], indptr, dplen, 0)
+    g_rows = torch.zeros(B, N, shape.hidden, dtype=torch.float32, device=DEV)
+    tok_rows = torch.zeros(B, N, dtype=torch.int32, device=DEV)
+    emitted = []
+    for b in range(B):                                   # prefill one sequence at a time into its slice of the caches
+        kvb = E.KVCache(ks, vs, indptr[b:b + 2], plen[b:b + 1], 0)
+        dkvb = E.KVCache([dk], [dv], indptr[b:b + 2], dplen[b:b + 1], 0)
+        g_last, logits = E.eagle3_prefill(ctx, torch.as_tensor(prompts[b], dtype=torch.int32, device=DEV), kvb, dkvb)
+        root = int(torch.argmax(logits))
+        assert root == refs[b][0]
+        g_rows[b, 0], tok_rows[b, 0] = g_last, root
+        emitted.append([root])
+    n_new = i32([1] * B)
+    parent = i32(np.tile(np.arange(-1, L), (B, 1)))
+    wanted = [[3, 0, 2, 1], [1, 3, 0, 2], [0, 2, 3, 3]]
+    accepted = [[] for _ in range(B)]
+    for step in range(n_steps):
+        rows1 = int(n_new.max())
+        kv.set_max_prefix_len(int(plen.max()))
+        dkv.set_max_prefix_len(int(dplen.max()))
+        chain_tok, chain_logp = E.eagle3_draft_chain(ctx, g_rows[:, :rows1].contiguous(), tok_rows[:, :rows1].contiguous(), n_new,
+                                                     dkv, L)
+        ct = chain_tok.cpu().numpy().copy()
+        for b in range(B):                               # plant the true continuation to the wanted depth
+            pos = len(emitted[b])
+            for lvl in range(wanted[b][step % 4]):
+                ct[b, 1 + lvl] = refs[b][pos + lvl]
+        tt = torch.as_tensor(ct, dtype=torch.int32, device=DEV)
+        logits, taps = E.eagle3_tree_verify(ctx, tt, parent, kv)
+        al, path, bonus = E.eagle3_accept(ctx, logits, tt, parent, 0.0)
+        prev = n_new.clone()
+        taps_new, tok_new, n_new = E.eagle3_commit(ctx, tt, path, al, bonus, kv, taps, N)
+        dplen += prev                                    # forward 1's real rows of every sequence stay in the draft cache
+        for b in range(B):
+            n = int(n_new[b])
+            assert n - 1 >= wanted[b][step % 4]
+            accepted[b].append(n - 1)
+            emitted[b] += tok_new[b, :n].cpu().numpy().tolist()
+            g_rows[b, :n] = E.eagle3_fuse_features(ctx, *[taps_new[t, b, :n].contiguous() for t in range(3)])
+        tok_rows = tok_new
+    for b in range(B):
+        assert emitted[b] == refs[b][:len(emitted[b])], b
+        assert max(accepted[b]) == L and min(accepted[b]) == 0
+    print("batched chain decoding: accepted lengths per sequence", accepted)

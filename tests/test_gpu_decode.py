@@ -309,3 +309,39 @@ def test_batched_chain_decoding_equals_plain_greedy_decoding_per_sequence():
         assert emitted[b] == refs[b][:len(emitted[b])], b
         assert max(accepted[b]) == L and min(accepted[b]) == 0
     print("batched chain decoding: accepted lengths per sequence", accepted)
+
+
+def test_prefill_bf16_two_chunks_matches_the_oracle():
+    """bf16 storage: a 70-token prompt in chunks of 64 + 6 against the oracle's prefill in bf16 mode (2-layer model, so
+    the single-layer tolerances apply): target cache, draft cache, fused feature and logits of the last position."""
+    import paper_2503_01840_amd as E
+    shape = S.get_shape("c2").with_(name="small", hidden=256, n_heads=4, n_kv_heads=2, intermediate=512, vocab=1024,
+                                    draft_vocab=512, n_layers=2, taps=(0, 1, 1))
+    model = PL.OracleModel(shape)
+    T = 70
+    prompt = S.uniform_ints(S.SEED + 3, S.TensorIds.PREFIX_TOK, (T,), 0, shape.vocab).numpy()
+    pre = O.prefill(shape, model.layer, model.globals(), prompt, rounding="bf16")
+    dw, emb = model.draft(), model.globals()["embed"]
+    g_all = O.fuse_features(dw["w_fc"], pre["taps"][0], pre["taps"][1], pre["taps"][2], rounding="bf16")
+    Kd = np.zeros((T - 1, shape.n_kv_heads, shape.head_dim)); Vd = np.zeros_like(Kd)
+    O.draft_forward(shape, dw, emb, g_all[:T - 1], prompt[1:], np.arange(T - 1), Kd, Vd, 0, 0,
+                    np.tril(np.ones((T - 1, T - 1), dtype=bool)), O.bf16_round)
+    ctx = E.Eagle3Context(shape, max_batch=1, max_nodes=64, max_depth=4, max_topk=4, max_new=64, device=DEV)
+    W = PL.device_weights(shape, device=DEV)
+    ctx.set_weights(W["target"], W["draft"])
+    cap = T + 16
+    z = lambda: torch.zeros(cap, shape.n_kv_heads, shape.head_dim, dtype=torch.bfloat16, device=DEV)
+    ks, vs = [z() for _ in range(shape.n_layers)], [z() for _ in range(shape.n_layers)]
+    i32 = lambda v: torch.tensor(v, dtype=torch.int32, device=DEV)
+    kv = E.KVCache(ks, vs, i32([0, cap]), i32([0]), 0)
+    dkv = E.KVCache([z()], [z()], i32([0, cap]), i32([0]), 0)
+    g_last, logits = E.eagle3_prefill(ctx, torch.as_tensor(prompt, dtype=torch.int32, device=DEV), kv, dkv)
+    torch.cuda.synchronize()
+    assert int(kv.prefix_len[0]) == T and int(dkv.prefix_len[0]) == T - 1
+    for l in range(shape.n_layers):
+        assert np.max(np.abs(ks[l][:T].float().cpu().numpy() - pre["k_new"][l])) < 4e-2, l      # one bf16 ulp at |k| < 8
+        assert np.max(np.abs(vs[l][:T].float().cpu().numpy() - pre["v_new"][l])) < 2e-2, l
+    assert np.max(np.abs(logits.cpu().numpy() - pre["logits"][-1])) < 2e-2
+    assert np.max(np.abs(g_last.cpu().numpy() - g_all[-1])) < 2e-2
+    assert np.max(np.abs(dkv.k_layers[0][:T - 1].float().cpu().numpy() - Kd)) < 4e-2
+    assert np.max(np.abs(dkv.v_layers[0][:T - 1].float().cpu().numpy() - Vd)) < 2e-2

@@ -1,0 +1,192 @@
+"""Seeded sweeps over shapes the hand-picked edge cases do not enumerate: node counts, prefix lengths, node orders
+and ragged batches drawn at random (fixed seed), every case compared with the oracle element by element."""
+import numpy as np
+import pytest
+import torch
+
+import eagle3_synth as S
+from oracle import eagle3_oracle as O
+import pipeline as PL
+from test_gpu_edges import SMALL, _ctx, _E
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _random_case(rs, salt, n_max):
+    N = int(rs.choice([1, 2, 3, 5, 8, 17, 31, 32, 33, 47, 63, 64])) if rs.rand() < 0.5 else int(rs.randint(1, n_max + 1))
+    N = min(N, n_max)
+    while True:                                               # a depth / fan-out limit the node count fits under
+        max_depth, max_children = int(rs.randint(1, 9)), int(rs.randint(1, 11))
+        if sum(max_children ** j for j in range(max_depth + 1)) >= 2 * N:
+            break
+    parent = S.random_tree(S.SEED, 300 + salt, N, max_depth, max_children)[0]
+    order = rs.choice(["level", "dfs", "mixed"])
+    if order != "level" and N > 2:
+        parent = S.reorder_tree(parent, order)[0]
+    return np.asarray(parent, dtype=np.int32)
+
+
+@pytest.mark.parametrize("shape", [S.get_shape("c1"), SMALL], ids=["fp32", "bf16"])
+def test_single_sequence_verify_and_accept_sweep(shape):
+    """24 random (tree, node order, prefix length) cases: logits, taps, written cache rows, then both acceptance walks
+    on the library's own logits against the oracle's walks on the same logits."""
+    E = _E()
+    rs = np.random.RandomState(11)
+    model = PL.OracleModel(shape)
+    ctx = _ctx(shape)
+    tol = 1e-4 if shape.dtype == "fp32" else 2e-2
+    for i in range(24):
+        parent = _random_case(rs, i, 64)
+        N = len(parent)
+        P = int(rs.choice([0, 1, 63, 64, 65, 127, 128, 129])) if rs.rand() < 0.4 else int(rs.randint(0, 400))
+        toks = S.uniform_ints(S.SEED + 500 + i, S.TensorIds.TREE_TOK, (N,), 0, shape.vocab).numpy()
+        pairs = [S.kv_layer(shape, l, P, seed=S.SEED + 500 + i) for l in range(shape.n_layers)]
+        ref = O.tree_verify(shape, model.layer, model.globals(), toks, parent,
+                            lambda l: tuple(O.as_f64(t) for t in pairs[l]), rounding=model.rounding)
+        ks, vs, indptr, plen, _ = PL.device_kv(pairs, N, DEV)
+        kv = E.KVCache(ks, vs, indptr, plen, P)
+        tt = torch.as_tensor(toks, dtype=torch.int32, device=DEV)[None]
+        pp = torch.as_tensor(parent, dtype=torch.int32, device=DEV)[None]
+        logits, taps = E.eagle3_tree_verify(ctx, tt, pp, kv)
+        torch.cuda.synchronize()
+        case = (i, N, P)
+        assert np.max(np.abs(logits[0].cpu().numpy() - ref["logits"])) < tol, case
+        assert np.max(np.abs(taps[:, 0].cpu().numpy() - ref["taps"])) < tol, case
+        for l in range(shape.n_layers):
+            assert np.max(np.abs(ks[l][P:].float().cpu().numpy() - ref["k_new"][l])) < tol, case
+            assert np.max(np.abs(vs[l][P:].float().cpu().numpy() - ref["v_new"][l])) < tol, case
+        lg = logits[0].cpu().numpy()
+        al, gp, bonus = E.eagle3_accept(ctx, logits, tt, pp, 0.0)
+        n_acc, rpath, rbonus = O.accept_greedy(lg.astype(np.float64), toks, parent)   # same fp32 values: no tolerance
+        assert int(al[0]) == n_acc and int(bonus[0]) == rbonus, case
+        assert gp[0].cpu().numpy().tolist() == rpath + [-1] * (N - len(rpath)), case
+        U = S.uniform01(S.SEED + i, S.TensorIds.UNIFORMS, (1, 2 * N))
+        al, gp, bonus = E.eagle3_accept(ctx, logits, tt, pp, 1.0, U.to(DEV))
+        n_acc, rpath, rbonus, margin, info = O.accept_stochastic(lg.astype(np.float64), toks, parent, 1.0,
+                                                                 U[0].double().numpy(), return_info=True)
+        if info["margin_children"] > 1e-5:
+            assert int(al[0]) == n_acc, case
+            assert gp[0].cpu().numpy().tolist()[:len(rpath)] == rpath, case
+            assert O.bonus_admissible(info, int(bonus[0]), 2e-5), case
+
+
+def test_ragged_batch_verify_sweep():
+    """8 random batches (2..12 sequences, 1..16 nodes, prefix lengths 0..300 with spare slots between the sequences),
+    every sequence compared with the single-sequence oracle."""
+    E = _E()
+    shape = SMALL
+    rs = np.random.RandomState(12)
+    model = PL.OracleModel(shape)
+    for i in range(8):
+        B, N = int(rs.randint(2, 13)), int(rs.randint(1, 17))
+        ctx = _ctx(shape, max_batch=B, max_nodes=N)
+        plens = [int(x) for x in rs.randint(0, 301, size=B)]
+        spare = [int(x) for x in rs.randint(0, 5, size=B)]
+        parents = np.stack([S.random_tree(S.SEED, 700 + 16 * i + b, N, 5, 4)[0] for b in range(B)]).astype(np.int32)
+        toks = S.uniform_ints(S.SEED + 40 + i, S.TensorIds.TREE_TOK, (B, N), 0, shape.vocab).numpy()
+        indptr = np.zeros(B + 1, dtype=np.int64)
+        indptr[1:] = np.cumsum(np.array(plens) + N + np.array(spare))
+        total = int(indptr[-1])
+        ks, vs = zip(*[tuple(t.to(DEV) for t in S.kv_layer(shape, l, total)) for l in range(shape.n_layers)])
+        kv = E.KVCache(ks, vs, torch.as_tensor(indptr, dtype=torch.int32, device=DEV),
+                       torch.tensor(plens, dtype=torch.int32, device=DEV), max(plens))
+        logits, taps = E.eagle3_tree_verify(ctx, torch.as_tensor(toks, dtype=torch.int32, device=DEV),
+                                            torch.as_tensor(parents, dtype=torch.int32, device=DEV), kv)
+        torch.cuda.synchronize()
+        for b in range(B):
+            base, P = int(indptr[b]), plens[b]
+            ref = O.tree_verify(shape, model.layer, model.globals(), toks[b], parents[b],
+                                lambda l: tuple(O.as_f64(t) for t in S.kv_layer(shape, l, P, first_slot=base)),
+                                rounding="bf16")
+            case = (i, B, N, b, P)
+            assert np.max(np.abs(logits[b].cpu().numpy() - ref["logits"])) < 2e-2, case
+            assert np.max(np.abs(taps[:, b].cpu().numpy() - ref["taps"])) < 2e-2, case
+            for l in range(shape.n_layers):
+                got_k = ks[l][base + P:base + P + N].float().cpu().numpy()
+                assert np.max(np.abs(got_k - ref["k_new"][l])) < 2e-2, case
+
+
+def test_commit_sweep_random_paths():
+    """10 random batches: every sequence commits a random root path of a random tree (accept lengths 0 .. depth);
+    rows of every layer, gathered features, following tokens and advanced lengths are all exact copies."""
+    E = _E()
+    shape = SMALL.with_(name="small3", n_layers=3, taps=(0, 1, 2))
+    rs = np.random.RandomState(13)
+    for i in range(10):
+        B, N = int(rs.randint(1, 9)), int(rs.choice([1, 2, 7, 16, 33, 64]))
+        ctx = _ctx(shape, weights=False, max_batch=B, max_nodes=N)
+        plens = rs.randint(0, 200, size=B)
+        indptr = np.zeros(B + 1, dtype=np.int64)
+        indptr[1:] = np.cumsum(plens + N + rs.randint(0, 4, size=B))
+        total = int(indptr[-1])
+        ks, vs = zip(*[tuple(t.to(DEV) for t in S.kv_layer(shape, l, total, seed=S.SEED + i)) for l in range(shape.n_layers)])
+        k0 = [k.clone() for k in ks]; v0 = [v.clone() for v in vs]
+        plen_d = torch.as_tensor(plens, dtype=torch.int32, device=DEV)
+        kv = E.KVCache(ks, vs, torch.as_tensor(indptr, dtype=torch.int32, device=DEV), plen_d, int(plens.max()))
+        paths, parents = [], []
+        for b in range(B):
+            depth_cap = max(1, min(8, N - 1))
+            parent = S.random_tree(S.SEED, 900 + 16 * i + b, N, depth_cap, 10)[0] if N > 1 else np.array([-1], dtype=np.int32)
+            if N > 2 and rs.rand() < 0.5:
+                parent = S.reorder_tree(parent, "mixed")[0]
+            all_paths = O.ancestor_paths(parent)
+            paths.append([int(x) for x in all_paths[int(rs.randint(N))]])
+            parents.append(parent)
+        path = np.full((B, N), -1, dtype=np.int32)
+        for b, p in enumerate(paths):
+            path[b, :len(p)] = p
+        al = torch.tensor([len(p) - 1 for p in paths], dtype=torch.int32, device=DEV)
+        tok = S.uniform_ints(S.SEED + i, S.TensorIds.TREE_TOK, (B, N), 0, shape.vocab).to(DEV)
+        bonus = torch.as_tensor(rs.randint(0, shape.vocab, size=B), dtype=torch.int32, device=DEV)
+        taps = S.normal(S.SEED + i, S.TensorIds.TAPS, (3, B, N, shape.hidden)).to(DEV)
+        rows = max(len(p) for p in paths)
+        dpl0 = rs.randint(0, 50, size=B)
+        dpl = torch.as_tensor(dpl0, dtype=torch.int32, device=DEV)
+
+        class _D:                                   # only the draft prefix lengths are touched
+            prefix_len = dpl
+        taps_new, tok_new, n_new = E.eagle3_commit(ctx, tok, torch.as_tensor(path, device=DEV), al, bonus, kv, taps, rows,
+                                                   draft_kv=_D, draft_rows=2)
+        torch.cuda.synchronize()
+        assert n_new.cpu().tolist() == [len(p) for p in paths], i
+        assert plen_d.cpu().tolist() == (plens + np.array([len(p) for p in paths])).tolist(), i
+        assert dpl.cpu().tolist() == (dpl0 + 2).tolist(), i
+        for b, p in enumerate(paths):
+            first = int(indptr[b] + plens[b])
+            assert tok_new[b, :len(p)].cpu().tolist() == [int(tok[b, q]) for q in p[1:]] + [int(bonus[b])], (i, b)
+            assert torch.equal(taps_new[:, b, :len(p)], taps[:, b, p]), (i, b)
+            for l in range(shape.n_layers):
+                for cur, old in ((ks[l], k0[l]), (vs[l], v0[l])):
+                    assert torch.equal(cur[first:first + len(p)], old[first + torch.as_tensor(p, device=DEV)]), (i, b, l)
+                    assert torch.equal(cur[int(indptr[b]):first], old[int(indptr[b]):first]), (i, b, l)
+
+
+@pytest.mark.parametrize("shape", [S.get_shape("c1"), SMALL], ids=["fp32", "bf16"])
+def test_draft_expand_sweep(shape):
+    """12 random (new rows, depth, top-k, tree size, context length) draws: the tree is bit-compared with the oracle
+    (which follows the library's choice only where two candidates are closer than the tolerance), scores by value."""
+    E = _E()
+    rs = np.random.RandomState(14)
+    model = PL.OracleModel(shape)
+    ctx = _ctx(shape)
+    tol = 1e-4 if shape.dtype == "fp32" else 2e-2
+    for i in range(12):
+        n_new, D, K = int(rs.randint(1, 9)), int(rs.randint(1, 9)), int(rs.randint(1, 9))
+        pool = 1 + K + (D - 1) * K * K
+        N = int(rs.randint(2, min(64, pool) + 1))
+        inp = PL.synthetic_step_inputs(shape, seed=S.SEED + 60 + i, n_new=n_new, prefix=int(rs.randint(0, 200)) + n_new)
+        ks, vs, indptr, plen, P = PL.device_kv([inp["draft_kv"]], n_new + (D - 1) * K, DEV)
+        got = E.eagle3_draft_expand(ctx, inp["g_new"].to(DEV), inp["tok_new"].to(DEV), E.KVCache(ks, vs, indptr, plen, P),
+                                    D, K, N, debug=True)
+        torch.cuda.synchronize()
+        got = {k: v.cpu().numpy() for k, v in got.items()}
+        ref = PL.oracle_draft(shape, model, inp, D, K, N, tol=tol / 2,
+                              follow={"pool_tok": got["pool_tok"], "frontier": got["frontier"], "chosen": got["chosen"]})
+        case = (i, n_new, D, K, N)
+        if ref["min_gap"] > tol / 2:
+            assert ref["n_followed"] == 0, case
+        for key in ("tree_tok", "parent", "depth", "chosen"):
+            assert np.array_equal(got[key], ref[key]), (case, key)
+        assert np.max(np.abs(got["score"] - ref["score"])) < tol, case
+        assert all(got["parent"][j] < j for j in range(1, N)) and got["parent"][0] == -1, case

@@ -33,8 +33,9 @@ mask form == explicit-ancestor-path brute force; fusion == a matmul with block-i
 cases; draft layer against composed library modules and the one-at-a-time == sequence
 invariant; expansion against brute-force enumeration of the full K-ary tree; greedy walk
 against autoregressive argmax decoding; stochastic walk by chi-square on a tiny vocabulary
-and the closed form P(emit x) = p(x).  The bf16 rounding points themselves have no
-external pin beyond the stated tolerance: "parity unpinned" for that detail.
+and the closed form P(emit x) = p(x).  The bf16 rounding points (operands of every weight
+product, rotated queries / keys and values; nothing else) are pinned against the library model
+with torch's bfloat16 cast hooked onto exactly those operands, with a leave-one-out control.
 """
 from __future__ import annotations
 

@@ -44,19 +44,10 @@ def test_fusion_is_a_matmul_on_the_concatenation_low_mid_high():
     np.testing.assert_allclose(O.fuse_features(np.hstack([I, 2 * I, 3 * I]), l, m, h), l + 2 * m + 3 * h, atol=1e-12)
 
 
-def test_draft_layer_against_composed_library_modules():
-    """q/k/v read the 2k-wide [norm(e); norm(f)]; the residual carries f; then a LLaMA MLP block; the
-    LM head reads the final-normed output.  Library attention/MLP/norm/rotary modules do the arithmetic."""
-    shape = SMALL
-    dwt, dw, emb = _draft(shape)
-    n_ctx, M = 13, 6
-    Kc, Vc = _ctx(shape, n_ctx, n_ctx + M)
-    f = O.as_f64(S.normal(S.SEED, S.TensorIds.G_NEW, (M, shape.hidden)))
-    tok = S.uniform_ints(S.SEED, S.TensorIds.TOK_NEW, (M,), 0, shape.vocab).numpy()
-    pos = n_ctx + np.arange(M)
-    a, z = O.draft_forward(shape, dw, emb, f, tok, pos, Kc, Vc, n_ctx, n_ctx, np.tril(np.ones((M, M), dtype=bool)),
-                           lambda x: x)
-
+def _library_draft_layer(shape, dwt, emb, f, tok, pos, Kc, Vc, n_ctx, cast=lambda t: t):
+    """The draft layer composed from the library's attention / MLP / norm / rotary modules; `cast` is applied to the
+    operand of every weight product and to the three attention operands.  Returns (a, z, rotated keys) as NumPy."""
+    M = len(tok)
     cfg = hf_config(shape, 1)
     k2 = 2 * shape.hidden
     att = LlamaAttention(cfg, 0).double().eval()
@@ -80,26 +71,88 @@ def test_draft_layer_against_composed_library_modules():
         # splice the context in through a cache object: simplest is to call its pieces with full K/V.
         ft = torch.from_numpy(f)[None]
         e = torch.from_numpy(emb)[torch.from_numpy(tok).long()][None]
-        u = torch.cat([norms["norm_embed"](e), norms["norm_feat"](ft)], -1)
+        u = cast(torch.cat([norms["norm_embed"](e), norms["norm_feat"](ft)], -1))
         cos, sin = LlamaRotaryEmbedding(cfg)(u, torch.from_numpy(pos)[None])
         from transformers.models.llama.modeling_llama import apply_rotary_pos_emb, eager_attention_forward
         H, Hkv, d = shape.n_heads, shape.n_kv_heads, shape.head_dim
         q = att.q_proj(u).view(1, M, H, d).transpose(1, 2)
         kk = att.k_proj(u).view(1, M, Hkv, d).transpose(1, 2)
-        vv = att.v_proj(u).view(1, M, Hkv, d).transpose(1, 2)
+        vv = cast(att.v_proj(u).view(1, M, Hkv, d).transpose(1, 2))
         q, kk = apply_rotary_pos_emb(q, kk, cos.double(), sin.double())
+        q, kk = cast(q), cast(kk)
         Kfull = torch.cat([torch.from_numpy(Kc[:n_ctx]).permute(1, 0, 2)[None], kk], 2)
         Vfull = torch.cat([torch.from_numpy(Vc[:n_ctx]).permute(1, 0, 2)[None], vv], 2)
         mask = torch.zeros(1, 1, M, n_ctx + M, dtype=torch.float64)
         mask[0, 0, :, n_ctx:] = torch.triu(torch.full((M, M), float("-inf"), dtype=torch.float64), 1)
         ao, _ = eager_attention_forward(att, q, Kfull, Vfull, mask, scaling=d ** -0.5)
-        y1 = ft + att.o_proj(ao.reshape(1, M, H * d))
-        a_ref = y1 + mlp(norms["norm_mlp"](y1))
-        z_ref = torch.nn.functional.linear(norms["final_norm"](a_ref), dwt["lm_head"].double())
-    np.testing.assert_allclose(a, a_ref[0].numpy(), atol=HF_ATOL, rtol=0)
-    np.testing.assert_allclose(z, z_ref[0].numpy(), atol=HF_ATOL, rtol=0)
+        y1 = ft + att.o_proj(cast(ao.reshape(1, M, H * d)))
+        n2 = cast(norms["norm_mlp"](y1))
+        a_ref = y1 + mlp.down_proj(cast(mlp.act_fn(mlp.gate_proj(n2)) * mlp.up_proj(n2)))
+        z_ref = torch.nn.functional.linear(cast(norms["final_norm"](a_ref)), dwt["lm_head"].double())
+    return a_ref[0].numpy(), z_ref[0].numpy(), kk[0].permute(1, 0, 2).numpy()
+
+
+def _draft_case(shape):
+    dwt, dw, emb = _draft(shape)
+    n_ctx, M = 13, 6
+    Kc, Vc = _ctx(shape, n_ctx, n_ctx + M)
+    f = O.as_f64(S.normal(S.SEED, S.TensorIds.G_NEW, (M, shape.hidden)))
+    tok = S.uniform_ints(S.SEED, S.TensorIds.TOK_NEW, (M,), 0, shape.vocab).numpy()
+    pos = n_ctx + np.arange(M)
+    return dwt, dw, emb, n_ctx, M, Kc, Vc, f, tok, pos
+
+
+def test_draft_layer_against_composed_library_modules():
+    """q/k/v read the 2k-wide [norm(e); norm(f)]; the residual carries f; then a LLaMA MLP block; the
+    LM head reads the final-normed output.  Library attention/MLP/norm/rotary modules do the arithmetic."""
+    shape = SMALL
+    dwt, dw, emb, n_ctx, M, Kc, Vc, f, tok, pos = _draft_case(shape)
+    a, z = O.draft_forward(shape, dw, emb, f, tok, pos, Kc, Vc, n_ctx, n_ctx, np.tril(np.ones((M, M), dtype=bool)),
+                           lambda x: x)
+    a_ref, z_ref, k_ref = _library_draft_layer(shape, dwt, emb, f, tok, pos, Kc, Vc, n_ctx)
+    np.testing.assert_allclose(a, a_ref, atol=HF_ATOL, rtol=0)
+    np.testing.assert_allclose(z, z_ref, atol=HF_ATOL, rtol=0)
     # the keys this call cached are the rotated ones the library attention used
-    np.testing.assert_allclose(Kc[n_ctx:n_ctx + M], kk[0].permute(1, 0, 2).numpy(), atol=HF_ATOL, rtol=0)
+    np.testing.assert_allclose(Kc[n_ctx:n_ctx + M], k_ref, atol=HF_ATOL, rtol=0)
+
+
+def test_draft_layer_bf16_rounding_points_are_the_operands_of_every_product():
+    """WHERE the draft layer's bf16 mode rounds: the concatenated normed input of q/k/v, rotated queries and keys,
+    values, the attention output before the output projection, the normed input of gate/up, gate * up before the
+    down projection, the normed input of the LM head; the residual (the feature) and `a` stay unrounded.  Reference:
+    the library modules with torch's bfloat16 cast on exactly those operands; control: the oracle with any one of its
+    rounding points left out misses by a wide margin."""
+    shape = SMALL
+    dwt, dw, emb, n_ctx, M, Kc, Vc, f, tok, pos = _draft_case(shape)
+    a_ref, z_ref, k_ref = _library_draft_layer(shape, dwt, emb, f, tok, pos, Kc, Vc, n_ctx,
+                                               cast=lambda t: t.float().bfloat16().double())
+
+    def run(rd):
+        K2, V2 = Kc.copy(), Vc.copy()
+        a, z = O.draft_forward(shape, dw, emb, f, tok, pos, K2, V2, n_ctx, n_ctx, np.tril(np.ones((M, M), dtype=bool)), rd)
+        return a, z, K2[n_ctx:n_ctx + M]
+    a, z, k_new = run(O.bf16_round)
+    sa, sz = np.sqrt(np.mean(a_ref ** 2)), np.sqrt(np.mean(z_ref ** 2))
+    err_a, err_z = np.max(np.abs(a - a_ref)), np.max(np.abs(z - z_ref))
+    assert err_a < 2e-4 * sa and err_z < 2e-4 * sz, (err_a, sa, err_z, sz)
+    assert np.max(np.abs(k_new - k_ref)) == 0.0                # the cached keys are bf16 values on both sides
+    calls = [0]
+
+    def counting(x):
+        calls[0] += 1
+        return O.bf16_round(x)
+    run(counting)
+    assert calls[0] == 8                                       # u, q, k, v, attention output, n2, gate * up, final norm
+    worst = np.inf
+    for skip in range(calls[0]):
+        i = [0]
+
+        def leave_one_out(x):
+            i[0] += 1
+            return x if i[0] - 1 == skip else O.bf16_round(x)
+        a2, z2, _ = run(leave_one_out)
+        worst = min(worst, max(np.max(np.abs(a2 - a_ref)) / sa, np.max(np.abs(z2 - z_ref)) / sz))
+    assert worst > 10 * max(err_a / sa, err_z / sz, 1e-6), worst
 
 
 def test_draft_rows_one_at_a_time_equal_one_causal_sequence():

@@ -189,3 +189,83 @@ def test_bf16_mode_stays_within_the_stated_budget_of_fp64_on_tiny_bf16_model():
     a = O.tree_verify(shape, lambda l: layers[l], tg, toks, parent, kv, rounding="none")
     b = O.tree_verify(shape, lambda l: layers[l], tg, toks, parent, kv, rounding="bf16")
     assert 0 < np.max(np.abs(a["logits"] - b["logits"])) < 2e-2
+
+
+def _library_forward_rounding_operands(shape, layers, tg, toks, mask=None, pos=None):
+    """The library model with torch's bfloat16 cast applied to every operand of a weight product (the input of every
+    Linear) and to the three attention operands (rotated queries and keys, values): built from hooks on the library's
+    own modules, it shares nothing with the oracle's layer code."""
+    import transformers.models.llama.modeling_llama as ML
+    cast = lambda t: t.float().bfloat16().double()
+    model = hf_model(shape, layers, tg)
+    hooks = []
+    for mod in model.modules():
+        if isinstance(mod, torch.nn.Linear):
+            hooks.append(mod.register_forward_pre_hook(lambda m, args: (cast(args[0]),) + tuple(args[1:])))
+    for lyr in model.model.layers:
+        hooks.append(lyr.self_attn.v_proj.register_forward_hook(lambda m, a, out: cast(out)))
+    rotary = ML.apply_rotary_pos_emb
+
+    def rounded_rotary(*a, **kw):
+        q, k = rotary(*a, **kw)
+        return cast(q), cast(k)
+    ML.apply_rotary_pos_emb = rounded_rotary
+    try:
+        return hf_forward(model, toks, mask, pos)
+    finally:
+        ML.apply_rotary_pos_emb = rotary
+        for h in hooks:
+            h.remove()
+
+
+def test_bf16_rounding_points_are_the_operands_of_every_product():
+    """Pins WHERE the oracle's bf16 mode rounds: at the operands of every weight product and of attention (queries
+    and keys after the rotation, values), nowhere else: residual stream, norm arithmetic, scores and softmax weights
+    stay unrounded.  Reference: the library model with torch's cast hooked onto exactly those operands.  Both sides
+    are fp64 except the library's fp32 softmax and rotary tables (1e-7), which can move a value across a bf16 rounding
+    boundary now and then; such a flip changes one operand entry by one unit in the last place, while a rounding
+    point that is missing, extra or misplaced changes every entry of a tensor: the control below shows the gap."""
+    shape = GQA.with_(dtype="bf16")
+    layers = [S.layer_weights(shape, l) for l in range(shape.n_layers)]
+    tg = S.target_globals(shape)
+    L64, tg64 = [O.weights_f64(W) for W in layers], O.weights_f64(tg)
+    empty = np.zeros((0, shape.n_kv_heads, shape.head_dim))
+    n_prefix = 12
+    parent, depth = S.random_tree(S.SEED, 5, 20, 4, 3)
+    N, T = len(parent), n_prefix + len(parent)
+    # the prefix as a chain in front of the tree: one tree of T nodes over an empty cache
+    full_parent = np.concatenate([np.arange(-1, n_prefix - 1), [n_prefix - 1 if p < 0 else n_prefix + p for p in parent]])
+    toks = S.uniform_ints(S.SEED + 9, S.TensorIds.PREFIX_TOK, (T,), 0, shape.vocab).numpy()
+    mask = O.ancestor_mask(full_parent)
+    pos = O.tree_depth(full_parent)
+    logits, hid = _library_forward_rounding_operands(shape, layers, tg, toks, mask, pos)
+
+    def run(rounding):
+        return O.tree_verify(shape, lambda l: L64[l], tg64, toks, full_parent, lambda l: (empty, empty),
+                             rounding=rounding, keep_hidden=True)
+    out = run("bf16")
+    scale = np.sqrt(np.mean(logits ** 2))
+    err = np.max(np.abs(out["logits"] - logits))
+    assert err < 2e-4 * scale, (err, scale)
+    for l in range(shape.n_layers):
+        s = np.sqrt(np.mean(hid[l] ** 2))
+        assert np.max(np.abs(out["hidden"][l + 1] - hid[l])) < 2e-4 * s, l
+    # control: the same oracle with any ONE of its rounding points left out is off by far more than that
+    n_calls = [0]
+
+    def counting(a):
+        n_calls[0] += 1
+        return O.bf16_round(a)
+    run(counting)
+    total = n_calls[0]
+    assert total == 7 * shape.n_layers + 1                     # per layer: n1, q, k, v, attention output, n2, gate * up; final norm
+    worst = np.inf
+    for skip in range(total):
+        i = [0]
+
+        def leave_one_out(a):
+            i[0] += 1
+            return a if i[0] - 1 == skip else O.bf16_round(a)
+        worst = min(worst, np.max(np.abs(run(leave_one_out)["logits"] - logits)))
+    assert worst > 10 * max(err, 1e-6), (worst, err)
+    print(f"rounding-point pin: max logit error {err:.2e} (logit RMS {scale:.2f}), smallest leave-one-out error {worst:.2e}")

@@ -110,15 +110,19 @@ def test_verify_trees_in_other_node_orders(order):
     assert np.max(np.abs(tp - tp0[:, old])) < TOL
 
 
-@pytest.mark.parametrize("n_seq", [48, 64])
-def test_batched_layer_teacher_forced_every_row_and_column(n_seq):
+@pytest.mark.parametrize("n_seq,n_nodes", [(48, 8), (64, 8), (64, 4)])
+def test_batched_layer_teacher_forced_every_row_and_column(n_seq, n_nodes):
     """One decoder layer + LM head at the 8B shape over n_seq x 8 = 384 / 512 node rows with ragged caches of
-    512..2048 tokens (the batched-verification launch shapes: every projection takes the many-row GEMM), the same
-    N(0, 8^2) residual rows on both sides, every output element compared."""
+    512..2048 tokens (the batched-verification launch shapes: every projection takes the many-row GEMM), and over
+    64 four-node chains = 256 rows (the verification launch of batched chain decoding); the same N(0, 8^2) residual
+    rows on both sides, every output element compared."""
     E = _E()
     full = S.get_shape("c4")
     rb = S.ragged_batch(full)
-    B, N = n_seq, full.n_nodes
+    B, N = n_seq, n_nodes
+    if N != full.n_nodes:                                  # chains instead of the stored trees
+        rb = dict(rb, parent=np.tile(np.arange(-1, N - 1, dtype=np.int32), (full.batch, 1)),
+                  tree_tok=np.ascontiguousarray(rb["tree_tok"][:, :N]))
     shape = full.with_(n_layers=1, taps=(0, 0, 0), batch=B)
     layer_id = 5
     W = S.layer_weights(full, layer_id)
@@ -133,8 +137,8 @@ def test_batched_layer_teacher_forced_every_row_and_column(n_seq):
     kv = E.KVCache([K_all], [V_all], torch.as_tensor(indptr, dtype=torch.int32, device=DEV),
                    torch.as_tensor(plen, dtype=torch.int32, device=DEV), int(plen.max()))
     x_in = S.normal(S.SEED + 11, S.TensorIds.TAPS, (B, N, full.hidden), 8.0)
-    tt = torch.as_tensor(rb["tree_tok"][:B], device=DEV)
-    pp = torch.as_tensor(rb["parent"][:B], device=DEV)
+    tt = torch.as_tensor(rb["tree_tok"][:B], dtype=torch.int32, device=DEV)
+    pp = torch.as_tensor(rb["parent"][:B], dtype=torch.int32, device=DEV)
     x_out, logits = E.eagle3_tree_verify_layers(ctx, tt, pp, kv, x_in.to(DEV), 0, 1, want_logits=True)
     torch.cuda.synchronize()
     x_out, logits = x_out.cpu().numpy(), logits.cpu().numpy()
@@ -208,3 +212,73 @@ def test_whole_step_chained_on_the_librarys_own_outputs():
     assert margin > 1e-4, "the seeded uniforms must not sit on a decision threshold"
     assert (int(al1[0]), int(bonus1[0])) == (n_acc, rbonus)
     assert path1[0].cpu().numpy().tolist() == rpath + [-1] * (N - len(rpath))
+
+
+def test_chain_drafting_at_the_batch_64_serving_shape():
+    """Batched chain drafting exactly as `bench.py --config chain` launches it: the 8B-shaped draft layer, 64 sequences
+    with ragged draft caches of 549..2029 tokens, one new position each, chains of 3 tokens.  Ten of the sequences
+    (shortest and longest context included) are run through the oracle one by one: the chain tokens must be the
+    oracle's wherever its arg-max margins exceed the stored score drift, cumulative log-probabilities and the cached
+    rows agree within the stored drift; the other sequences must be finite and identical run to run."""
+    E = _E()
+    shape = S.get_shape("c4")
+    L = 3
+    rb = S.ragged_batch(shape)
+    B = shape.batch
+    plen = rb["prefix_len"].astype(np.int64)
+    indptr = np.zeros(B + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum(plen + 8)
+    total = int(indptr[-1])
+    sub = shape.with_(n_layers=1, taps=(0, 0, 0))
+    ctx = E.Eagle3Context(sub, max_batch=B, max_nodes=8, max_depth=4, max_topk=2, max_new=8, device=DEV)
+    T = S.TensorIds
+    tg = {"embed": S.normal(S.SEED, T.EMBED, (shape.vocab, shape.hidden), 0.02, 0.0, torch.bfloat16, DEV),
+          "final_norm": S.normal(S.SEED, T.FINAL_NORM, (shape.hidden,), 0.02, 1.0, torch.bfloat16, DEV)}
+    tg["lm_head"] = tg["embed"]                     # never read by the draft call
+    ctx.set_weights({"layers": [S.layer_weights(sub, 0, device=DEV)], **tg}, S.draft_weights(shape, device=DEV))
+    K_all, V_all = S.kv_layer(shape, 0, total, draft=True)
+    i32 = lambda a: torch.as_tensor(np.asarray(a), dtype=torch.int32, device=DEV)
+    g = S.normal(S.SEED, T.G_NEW, (B, 1, shape.hidden))
+    tok = S.uniform_ints(S.SEED, T.TOK_NEW, (B, 1), 0, shape.vocab)
+    n_new = torch.ones(B, dtype=torch.int32, device=DEV)
+    runs = []
+    for _ in range(2):
+        Kd, Vd = K_all.to(DEV), V_all.to(DEV)
+        dkv = E.KVCache([Kd], [Vd], i32(indptr), i32(plen), int(plen.max()))
+        chain_tok, chain_logp = E.eagle3_draft_chain(ctx, g.to(DEV), tok.to(DEV), n_new, dkv, L)
+        torch.cuda.synchronize()
+        runs.append((chain_tok.cpu().numpy(), chain_logp.cpu().numpy(), Kd, Vd))
+    got_tok, got_logp, Kd, Vd = runs[0]
+    assert np.array_equal(got_tok, runs[1][0]) and np.array_equal(got_logp, runs[1][1])
+    assert torch.equal(Kd, runs[1][2]) and torch.equal(Vd, runs[1][3])
+    assert np.all(np.isfinite(got_logp)) and np.all(got_logp[:, 1:] < 0) and np.all(np.diff(got_logp, axis=1) <= 0)
+    assert np.array_equal(got_tok[:, 0], tok[:, 0].numpy())
+    print("chain bs64: GPU side done, running the oracle", flush=True)
+    model = PL.OracleModel(shape, cache_layers=False, lazy_embed=True)
+    dw, emb = model.draft(), model.embed()
+    _, level_tol = parity.draft_tolerances(parity.golden("c3"), S.get_shape("c3").depth)         # same draft shape
+    tie_tol = float(np.max(level_tol[:L]) / parity.MAX_FACTOR)   # the stored score drift of the three levels in use
+    sample = sorted({0, 9, 17, 26, 35, 44, 53, 63, int(np.argmin(plen)), int(np.argmax(plen))})
+    checked_tokens = 0
+    worst = np.zeros(L)
+    for b in sample:
+        lo, c = int(indptr[b]), int(plen[b])
+        Kc = np.zeros((c + L + 1, shape.n_kv_heads, shape.head_dim)); Vc = np.zeros_like(Kc)
+        Kc[:c], Vc[:c] = O.as_f64(K_all[lo:lo + c]), O.as_f64(V_all[lo:lo + c])
+        ref = O.draft_expand(shape, dw, emb, O.as_f64(g[b]), tok[b].numpy().astype(np.int64), Kc, Vc, c, L, 1, L + 1,
+                             rounding=model.rounding)
+        assert np.array_equal(ref["parent"], np.arange(-1, L))
+        if ref["min_gap"] > tie_tol:                 # every arg-max of this chain is clear of the score drift
+            assert np.array_equal(got_tok[b], ref["tree_tok"]), b
+            checked_tokens += 1
+            err = np.abs(got_logp[b, 1:] - ref["score"][1:])
+            worst = np.maximum(worst, err)
+            assert np.all(err <= level_tol[:L]), (b, err)
+            rows = slice(lo + c, lo + c + L)             # the root's row and the two drafted rows that were fed back
+            for cur, want in ((Kd, Kc), (Vd, Vc)):       # bf16 values on both sides: equal, or one unit in the last
+                d = cur[rows].float().cpu().numpy() - want[c:c + L]   # place apart (2^-4 at |x| in [8, 16)) where the input drifted
+                assert np.max(np.abs(d)) <= 0.125 and parity.rms(d) < parity.TOL, (b, np.max(np.abs(d)), parity.rms(d))
+        print(f"chain bs64: sequence {b} (context {c}) min arg-max gap {ref['min_gap']:.3f}", flush=True)
+    parity.report(f"chain bs64 draft: {checked_tokens} of {len(sample)} sampled chains clear of near-ties and identical; "
+                  f"log-prob error per level {np.round(worst, 5).tolist()}, allowed {np.round(level_tol[:L], 5).tolist()}")
+    assert checked_tokens >= len(sample) * 3 // 4

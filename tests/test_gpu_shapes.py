@@ -282,3 +282,58 @@ def test_chain_drafting_at_the_batch_64_serving_shape():
     parity.report(f"chain bs64 draft: {checked_tokens} of {len(sample)} sampled chains clear of near-ties and identical; "
                   f"log-prob error per level {np.round(worst, 5).tolist()}, allowed {np.round(level_tol[:L], 5).tolist()}")
     assert checked_tokens >= len(sample) * 3 // 4
+
+
+@pytest.mark.parametrize("name", ["c3", "c4"])
+def test_commit_at_full_shape(name):
+    """eagle3_commit over all 32 layers of the 8B-shaped caches: one sequence with a 60-node tree behind 4096 cached
+    tokens, and the ragged batch of 64 eight-node trees; random root paths; every moved row is an exact copy."""
+    E = _E()
+    shape = S.get_shape(name)
+    rs = np.random.RandomState(21)
+    if name == "c3":
+        B, N = 1, shape.n_nodes
+        plen = np.array([shape.prefix_lo], dtype=np.int64)
+        parents = [S.random_tree(S.SEED, 31, N, shape.depth, shape.topk)[0]]
+    else:
+        rb = S.ragged_batch(shape)
+        B, N = shape.batch, shape.n_nodes
+        plen = rb["prefix_len"].astype(np.int64)
+        parents = [rb["parent"][b] for b in range(B)]
+    ctx = E.Eagle3Context(shape, max_batch=B, max_nodes=N, max_depth=shape.depth, max_topk=shape.topk, max_new=8, device=DEV)
+    indptr = np.zeros(B + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum(plen + N)
+    total = int(indptr[-1])
+    paths = []
+    for b in range(B):
+        all_paths = O.ancestor_paths(parents[b])
+        deepest = max(all_paths, key=len)
+        paths.append([int(x) for x in (deepest if b % 4 == 0 else all_paths[int(rs.randint(N))])])
+    path = np.full((B, N), -1, dtype=np.int32)
+    for b, p in enumerate(paths):
+        path[b, :len(p)] = p
+    i32 = lambda a: torch.as_tensor(np.asarray(a), dtype=torch.int32, device=DEV)
+    ks, vs = zip(*[S.kv_layer(shape, l, total, device=DEV) for l in range(shape.n_layers)])
+    tails = [(torch.cat([k[int(indptr[b] + plen[b]):int(indptr[b + 1])] for b in range(B)]).clone(),
+              torch.cat([v[int(indptr[b] + plen[b]):int(indptr[b + 1])] for b in range(B)]).clone()) for k, v in zip(ks, vs)]
+    heads = [k[:int(plen[0])].clone() for k in ks[:2]]
+    plen_d = i32(plen)
+    kv = E.KVCache(ks, vs, i32(indptr), plen_d, int(plen.max()))
+    tok = S.uniform_ints(S.SEED, S.TensorIds.TREE_TOK, (B, N), 0, shape.vocab).to(DEV)
+    bonus = i32(rs.randint(0, shape.vocab, size=B))
+    taps = S.normal(S.SEED, S.TensorIds.TAPS, (3, B, N, shape.hidden), device=DEV)
+    rows = max(len(p) for p in paths)
+    taps_new, tok_new, n_new = E.eagle3_commit(ctx, tok, i32(path), i32([len(p) - 1 for p in paths]), bonus, kv, taps, rows)
+    torch.cuda.synchronize()
+    assert n_new.cpu().tolist() == [len(p) for p in paths]
+    assert plen_d.cpu().tolist() == (plen + np.array([len(p) for p in paths])).tolist()
+    for b, p in enumerate(paths):
+        first = int(indptr[b] + plen[b])
+        idx = torch.as_tensor(p, device=DEV) + b * N
+        assert tok_new[b, :len(p)].cpu().tolist() == [int(tok[b, q]) for q in p[1:]] + [int(bonus[b])], b
+        assert torch.equal(taps_new[:, b, :len(p)], taps[:, b, p]), b
+        for l in range(shape.n_layers):
+            assert torch.equal(ks[l][first:first + len(p)], tails[l][0][idx]), (b, l)
+            assert torch.equal(vs[l][first:first + len(p)], tails[l][1][idx]), (b, l)
+    for l in range(2):                                     # cached context untouched
+        assert torch.equal(ks[l][:int(plen[0])], heads[l])

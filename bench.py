@@ -129,6 +129,20 @@ def main():
         for i in range(4):
             parts[i] += ev[i].elapsed_time(ev[i + 1]) / reps
 
+    # the same step with the caches flushed before it (a 512 MiB fill between steps evicts the 256 MB memory-side cache
+    # and every L2), outside the timed region: back-to-back steps could otherwise find the first weights they read still
+    # cached from the previous step's end
+    flush = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+    cold_ms = 0.0
+    for i in range(reps):
+        flush.fill_(i & 0xFF)
+        ev[0].record()
+        step()
+        ev[4].record()
+        torch.cuda.synchronize()
+        cold_ms += ev[0].elapsed_time(ev[4]) / reps
+    del flush
+
     # per-launch kernel durations of the weight-streaming GEMMs (HIP events attached to every dispatch on the stream
     # in use), by kernel: 64-weight-row workgroups (q/k/v, o, down), 128-weight-row ones (gate/up, LM head), draft GEMMs
     ctx.profile_begin()
@@ -181,6 +195,7 @@ def main():
         "call_us": {"fuse_features": parts[0] * 1e3, "draft_expand": parts[1] * 1e3, "tree_verify": parts[2] * 1e3,
                     "accept_greedy_plus_stochastic": parts[3] * 1e3},
         "verify_tree_tokens_per_s": N / parts[2] * 1e3,
+        "ms_per_step_after_cache_flush": cold_ms,
         "roofline": roofline,
     }
 

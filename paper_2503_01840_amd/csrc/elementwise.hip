@@ -87,43 +87,52 @@ __global__ __launch_bounds__(256) void tree_prep_kernel(const int32_t* __restric
                                                        int32_t* __restrict__ depth, uint32_t* __restrict__ mask,
                                                        int32_t* __restrict__ slot, float* __restrict__ cs,
                                                        SeqInfo* __restrict__ seq) {
-  __shared__ int sdepth[64];
+  // Workgroup (b, y): every y walks sequence b's tree (parents staged in LDS: one memory round trip, then the walks
+  // stay on chip) and fills its share of the rotary table, whose sines and cosines are the bulk of the work; y = 0
+  // also writes the masks, depths, slots and the sequence record.
+  __shared__ int sdepth[64], spar[64];
   __shared__ int rank;
-  const int b = blockIdx.x, i = threadIdx.x, B = gridDim.x;
+  const int b = blockIdx.x, y = blockIdx.y, i = threadIdx.x, B = gridDim.x;
   const int P = prefix_len[b], base = kv_indptr[b];
-  // rank of this sequence by prefix length, longest first (ties: smaller index first): attention hands out its
-  // workgroups in that order, so that the long sequences start first and the short ones fill the tail
+  if (i < N) spar[i] = parent[b * N + i];
   if (i == 0) rank = 0;
   __syncthreads();
-  int longer = 0;
-  for (int o = i; o < B; o += 256) {
-    const int Po = prefix_len[o];
-    longer += (Po > P || (Po == P && o < b)) ? 1 : 0;
+  if (y == 0) {
+    // rank of this sequence by prefix length, longest first (ties: smaller index first): attention hands out its
+    // workgroups in that order, so that the long sequences start first and the short ones fill the tail
+    int longer = 0;
+    for (int o = i; o < B; o += 256) {
+      const int Po = prefix_len[o];
+      longer += (Po > P || (Po == P && o < b)) ? 1 : 0;
+    }
+    if (longer) atomicAdd(&rank, longer);
   }
-  if (longer) atomicAdd(&rank, longer);
-  __syncthreads();
-  if (i == 0) seq[rank].order = b;
   if (i < N) {
     uint32_t m[4] = {0u, 0u, 0u, 0u};
     int cur = i, dep = 0;
     for (int it = 0; it < N; ++it) {                     // bounded walk: malformed parents cannot loop
       m[cur >> 5] |= 1u << (cur & 31);
-      const int p = parent[b * N + cur];
+      const int p = spar[cur];
       if (p < 0 || p >= cur) break;
       cur = p;
       ++dep;
     }
     sdepth[i] = dep;
-    const int r = b * N + i;
-    depth[r] = dep;
-    slot[r] = base + P + i;
+    if (y == 0) {
+      const int r = b * N + i;
+      depth[r] = dep;
+      slot[r] = base + P + i;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) mask[r * 4 + w] = m[w];
+      for (int w = 0; w < 4; ++w) mask[r * 4 + w] = m[w];
+    }
   }
-  if (i == 0) { seq[b].kv_base = base; seq[b].n_prefix = P; seq[b].n_tail = N; }
   __syncthreads();
+  if (y == 0 && i == 0) {
+    seq[rank].order = b;
+    seq[b].kv_base = base; seq[b].n_prefix = P; seq[b].n_tail = N;
+  }
   const int half = d / 2;
-  for (int e = i; e < N * half; e += 256) {
+  for (int e = y * 256 + i; e < N * half; e += 256 * gridDim.y) {
     const int row = e / half, f = e % half;
     rope_entry(cs, b * N + row, f, d, P + sdepth[row], theta);
   }
@@ -318,7 +327,9 @@ hipError_t launch_tree_prep(const int32_t* parent, const int32_t* kv_indptr, con
                             int head_dim, float theta, int32_t* depth, uint32_t* mask, int32_t* slot, float* cs,
                             SeqInfo* seq, hipStream_t st) {
   if (N > 64) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(tree_prep_kernel, dim3(B), dim3(256), 0, st, parent, kv_indptr, prefix_len, N, head_dim, theta, depth,
+  // enough workgroups that each thread computes one or two table entries, no more than ~1024 workgroups in all
+  const int per_seq = std::max(1, std::min((N * (head_dim / 2) + 511) / 512, std::max(1, 1024 / B)));
+  hipLaunchKernelGGL(tree_prep_kernel, dim3(B, per_seq), dim3(256), 0, st, parent, kv_indptr, prefix_len, N, head_dim, theta, depth,
                      mask, slot, cs, seq);
   return hipGetLastError();
 }

@@ -211,33 +211,51 @@ __global__ __launch_bounds__(1024) void draft_rerank_kernel(DraftState s, const 
                                                            int32_t* __restrict__ chosen_dbg) {
   __shared__ float sc[MAX_POOL];
   __shared__ int16_t node_of[MAX_POOL];       // node id of a kept pool entry, -1 otherwise
+  __shared__ int16_t surv[MAX_POOL];          // pool ids that can still be among the best `keep`
+  __shared__ int16_t kept[64];                // the kept pool ids, in no particular order
+  __shared__ float bound_v;
+  __shared__ int bound_i, n_surv, n_kept;
   const int tid = threadIdx.x, keep = n_nodes - 1;
-  for (int e = tid; e < pool; e += 1024) sc[e] = s.pool_score[e];
+  for (int e = tid; e < pool; e += 1024) { sc[e] = s.pool_score[e]; node_of[e] = -1; }
+  if (tid == 0) { bound_v = -INFINITY; bound_i = INT_MAX; n_surv = 0; n_kept = 0; }
   __syncthreads();
-  for (int e = tid; e < pool; e += 1024) {
+  // In the order (score desc, pool id asc) the keep-th best of ANY subset bounds the answer from below: at least
+  // `keep` entries are not worse than it, so an entry worse than it cannot be kept.  The subset is the first 2 keep
+  // (at least 64) drafted entries: the early levels, whose cumulative scores are the highest.  Ranking by counting
+  // then only runs over the survivors.
+  const int m = min(pool - 1, max(2 * keep, 64));
+  if (m >= keep && tid >= 1 && tid <= m) {
+    const float se = sc[tid];
     int rank = 0;
-    if (e > 0)
-      for (int j = 1; j < pool; ++j) rank += better(sc[j], j, sc[e], e) ? 1 : 0;
-    node_of[e] = (e > 0 && rank < keep) ? 1 : 0;
+    for (int j = 1; j <= m; ++j) rank += better(sc[j], j, se, tid) ? 1 : 0;
+    if (rank == keep - 1) { bound_v = se; bound_i = tid; }
   }
   __syncthreads();
-  int my_node[(MAX_POOL + 1023) / 1024];
-#pragma unroll
-  for (int it = 0; it < (MAX_POOL + 1023) / 1024; ++it) {
-    const int e = tid + it * 1024;
-    my_node[it] = -1;
-    if (e < pool && e > 0 && node_of[e]) {
-      int before = 0;
-      for (int j = 1; j < e; ++j) before += node_of[j];
-      my_node[it] = 1 + before;                  // kept entries in ascending pool id
+  const float bv = bound_v;
+  const int bi = bound_i;
+  for (int e = tid; e < pool; e += 1024)
+    if (e > 0 && !better(bv, bi, sc[e], e)) surv[atomicAdd(&n_surv, 1)] = (int16_t)e;
+  __syncthreads();
+  const int T = n_surv;
+  for (int t = tid; t < T; t += 1024) {
+    const int e = surv[t];
+    const float se = sc[e];
+    int rank = 0;
+    for (int j = 0; j < T; ++j) {
+      const int o = surv[j];
+      rank += better(sc[o], o, se, e) ? 1 : 0;
     }
+    if (rank < keep) kept[atomicAdd(&n_kept, 1)] = (int16_t)e;
   }
   __syncthreads();
-#pragma unroll
-  for (int it = 0; it < (MAX_POOL + 1023) / 1024; ++it) {
-    const int e = tid + it * 1024;
-    if (e < pool) node_of[e] = e == 0 ? 0 : (int16_t)my_node[it];
+  // node ids: the kept entries in ascending pool id (the order they were drafted in), after the root
+  if (tid < n_kept) {
+    const int e = kept[tid];
+    int before = 0;
+    for (int j = 0; j < n_kept; ++j) before += kept[j] < e ? 1 : 0;
+    node_of[e] = (int16_t)(1 + before);
   }
+  if (tid == 0) node_of[0] = 0;
   __syncthreads();
   if (tid == 0) {
     tree_tok[0] = tok_new[n_new - 1];
@@ -384,7 +402,7 @@ hipError_t launch_draft_rerank(const DraftState& s, const int32_t* d2t, const in
                                int n_nodes, int32_t* tree_tok, int32_t* parent, int32_t* node_depth, float* cum_logprob,
                                int32_t* chosen_dbg, hipStream_t st) {
   const int pool = 1 + K + (depth - 1) * K * K;
-  if (pool > MAX_POOL || n_nodes - 1 > pool - 1) return hipErrorInvalidValue;
+  if (pool > MAX_POOL || n_nodes - 1 > pool - 1 || n_nodes - 1 > 64) return hipErrorInvalidValue;   // the kept list holds 64
   hipLaunchKernelGGL(draft_rerank_kernel, dim3(1), dim3(1024), 0, st, s, d2t, tok_new, n_new, pool, n_nodes, tree_tok,
                      parent, node_depth, cum_logprob, chosen_dbg);
   return hipGetLastError();

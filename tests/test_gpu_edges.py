@@ -274,3 +274,13 @@ def test_argument_checks_on_a_live_context():
     with pytest.raises(E.Eagle3Error) as e:
         E.eagle3_accept(ctx, torch.zeros(1, 4, shape.vocab, device=DEV), tt[:, :4].contiguous(), tt[:, :4].contiguous(), 1.0, None)
     assert e.value.code == -1
+
+
+def test_verify_against_a_long_context():
+    """20 003 cached tokens under a 60-node tree on the small bf16 model: 313 key tiles cut into dozens of key splits
+    (the split merge runs several rounds), prefix not a multiple of the tile; and 9 000 tokens under a 3-node tree."""
+    shape = SMALL
+    model = PL.OracleModel(shape)
+    ctx = _ctx(shape)
+    _verify_case(ctx, shape, model, S.random_tree(S.SEED, 61, 60, 8, 10)[0], 20003, seed_salt=31)
+    _verify_case(ctx, shape, model, S.random_tree(S.SEED, 62, 3, 2, 2)[0], 9000, seed_salt=32)

@@ -105,11 +105,12 @@ def test_verify_ragged_batch_matches_per_sequence_oracle():
 
 def test_verify_more_than_64_rows_uses_the_wide_gemm_path():
     """12 sequences x 8 nodes = 96 rows (the batched-verification GEMM tiling), 16 x 16 = 256 rows with a ragged tail;
-    176 and 225 rows take the one-row-block tiling of 129..256 rows with a partly empty block."""
+    176 and 225 rows take the one-row-block tiling of 129..256 rows with a partly empty block; 768 and 1024 rows span
+    three and four 256-row blocks."""
     E = _E()
     shape = SMALL
     model = PL.OracleModel(shape)
-    for B, N in ((12, 8), (16, 16), (5, 13), (11, 16), (15, 15)):
+    for B, N in ((12, 8), (16, 16), (5, 13), (11, 16), (15, 15), (24, 32), (64, 16)):
         ctx = _ctx(shape, max_batch=B, max_nodes=N)
         plens = [(37 * b + 11) % 150 for b in range(B)]
         parents = np.stack([S.random_tree(S.SEED, 80 + b, N, 4, 3)[0] for b in range(B)])

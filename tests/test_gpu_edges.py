@@ -143,7 +143,8 @@ def test_verify_33_to_64_rows_on_large_ragged_matrices():
         _verify_case(ctx, shape, model, S.random_tree(S.SEED, 40 + i, N, 6, 8)[0], 70 + i, seed_salt=20 + i)
 
 
-@pytest.mark.parametrize("n_new,D,K,N", [(8, 3, 3, 10), (1, 4, 1, 5), (2, 1, 4, 5), (1, 2, 16, 40), (3, 8, 2, 30)])
+@pytest.mark.parametrize("n_new,D,K,N", [(8, 3, 3, 10), (1, 4, 1, 5), (2, 1, 4, 5), (1, 2, 16, 40), (3, 8, 2, 30),
+                                          (2, 8, 16, 64)])          # the largest pool: 1809 candidates, 114 draft rows
 def test_draft_expand_shapes(n_new, D, K, N):
     E = _E()
     shape = SMALL

@@ -11,9 +11,10 @@ RMS_FACTOR, MAX_FACTOR = 1.5, 2.0
 
 
 def report(line):
-    """Measured figures: printed, and appended to gpurun_out/parity_errors.txt when that folder exists."""
+    """Measured figures: printed, and appended to parity_errors.txt in the run's output folder (PARITY_REPORT_DIR,
+    by default the untracked output folder at the repository root) when that folder exists."""
     print(line, flush=True)
-    out = os.path.join(os.path.dirname(GOLD), "..", "gpurun_out")
+    out = os.environ.get("PARITY_REPORT_DIR", os.path.join(os.path.dirname(GOLD), "..", "gpurun_out"))
     if os.path.isdir(out):
         with open(os.path.join(out, "parity_errors.txt"), "a") as f:
             f.write(line + "\n")

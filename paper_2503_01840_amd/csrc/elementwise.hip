@@ -197,7 +197,7 @@ __global__ __launch_bounds__(256) void pack3_kernel(const float* __restrict__ a,
                                                    const float* __restrict__ c, int k,
                                                    typename Act<BF16>::type* __restrict__ act) {
   const int r = blockIdx.x;
-  for (int j = threadIdx.x; j < k; j += 256) {
+  for (int j = blockIdx.y * 256 + threadIdx.x; j < k; j += 256 * gridDim.y) {
     Act<BF16>::store(act, r, j, 3 * k, a[(size_t)r * k + j]);
     Act<BF16>::store(act, r, k + j, 3 * k, b[(size_t)r * k + j]);
     Act<BF16>::store(act, r, 2 * k + j, 3 * k, c[(size_t)r * k + j]);
@@ -353,8 +353,9 @@ hipError_t launch_swiglu_f32(const float* gu, int R, int I, float* h, hipStream_
 }
 
 hipError_t launch_pack3(bool bf16, const float* a, const float* b, const float* c, int M, int k, void* act, hipStream_t st) {
-  if (bf16) hipLaunchKernelGGL(pack3_kernel<true>, dim3(M), dim3(256), 0, st, a, b, c, k, (bf16_t*)act);
-  else hipLaunchKernelGGL(pack3_kernel<false>, dim3(M), dim3(256), 0, st, a, b, c, k, (float*)act);
+  const dim3 grid(M, std::max(1, std::min(k / 512, 64 / std::max(M, 1))));   // few rows: several workgroups per row
+  if (bf16) hipLaunchKernelGGL(pack3_kernel<true>, grid, dim3(256), 0, st, a, b, c, k, (bf16_t*)act);
+  else hipLaunchKernelGGL(pack3_kernel<false>, grid, dim3(256), 0, st, a, b, c, k, (float*)act);
   return hipGetLastError();
 }
 

@@ -95,6 +95,13 @@ __global__ __launch_bounds__(64) void accept_walk_kernel(const float* __restrict
   const int my_par = lane < N ? parent[b * N + lane] : INT_MIN;
   const int my_tok = lane < N ? tree_tok[b * N + lane] : -1;
   if (lane < N) path[b * N + lane] = lane == 0 ? 0 : -1;
+  // what the child tests of the stochastic walk read, fetched for every node at once: the target's logit of the node's
+  // own token at its parent's row, and the node's uniform (one memory round trip instead of one per tested child)
+  float my_z = 0.f, my_u = 0.f;
+  if (!greedy && lane > 0 && lane < N && my_par >= 0 && my_par < lane) {
+    my_z = logits[((size_t)b * N + my_par) * V + min(max(my_tok, 0), V - 1)];
+    my_u = uniforms[(size_t)b * 2 * N + 2 * lane];
+  }
   int cur = 0, len = 0, bonus = 0;
   for (int step = 0; step < N; ++step) {
     const int row = b * N + cur;
@@ -133,9 +140,9 @@ __global__ __launch_bounds__(64) void accept_walk_kernel(const float* __restrict
       const int t = min(max(__shfl(my_tok, c, 64), 0), V - 1);
       bool is_struck = false;
       for (int j = 0; j < n_struck; ++j) is_struck |= struck[j] == t;
-      const float pt = expf(z[t] * inv_t - mx) / tot;
+      const float pt = expf(__shfl(my_z, c, 64) * inv_t - mx) / tot;
       const float thr = is_struck ? 0.f : pt / (1.f - rej);
-      const float u = uniforms[(size_t)b * 2 * N + 2 * c];
+      const float u = __shfl(my_u, c, 64);
       if (u < thr) { accepted = c; break; }
       if (!is_struck) {
         rej += pt;

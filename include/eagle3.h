@@ -42,8 +42,10 @@ enum {
 };
 
 /* Model and limits; copied at eagle3_create.
- * bf16 configurations require head_dim == 128 and hidden, intermediate multiples of 128, vocab and
- * draft_vocab multiples of 64; fp32 configurations accept any even head_dim <= 256 (slow,
+ * bf16 configurations require head_dim == 128 and hidden, intermediate multiples of 128; vocab and
+ * draft_vocab may be any size as long as no call runs more than 64 rows (max_batch * max_nodes <= 64
+ * and max_batch * max_new <= 64), otherwise they must be multiples of 4 (the many-row GEMM stores
+ * four outputs at a time); fp32 configurations accept any even head_dim <= 256 (slow,
  * exact-arithmetic kernels meant for small models). */
 typedef struct {
   int32_t hidden, n_heads, n_kv_heads, head_dim, intermediate, vocab, draft_vocab, n_layers;

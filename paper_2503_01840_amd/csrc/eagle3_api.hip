@@ -202,6 +202,9 @@ int eagle3_create(const eagle3_config* cfg, eagle3_ctx** out) {
   if (c.dtype == EAGLE3_BF16) {
     if (c.head_dim != 128 || c.hidden % 128 || c.intermediate % 128 || (c.n_heads * c.head_dim) % 128)
       return EAGLE3_E_SHAPE;
+    // launches of more than 64 rows go through the many-row GEMM, which stores four outputs at a time
+    const long many = std::max((long)c.max_batch * c.max_nodes, (long)c.max_batch * c.max_new);
+    if (many > 64 && (c.vocab % 4 || c.draft_vocab % 4)) return EAGLE3_E_SHAPE;
   } else {
     if (c.head_dim % 2 || c.head_dim > 256) return EAGLE3_E_SHAPE;
   }

@@ -66,7 +66,7 @@ def test_bf16_configuration_limits(L):
     ok = _cfg(dtype=Bd.EAGLE3_BF16, hidden=512, n_heads=4, n_kv_heads=2, head_dim=128, intermediate=1024)
     assert L.eagle3_create(C.byref(ok), C.byref(h)) == 0
     L.eagle3_destroy(h)
-    for bad in (dict(hidden=500), dict(intermediate=1000), dict(head_dim=64)):
+    for bad in (dict(hidden=500), dict(intermediate=1000), dict(head_dim=64), dict(vocab=1001, max_batch=4, max_nodes=32)):
         kw = dict(dtype=Bd.EAGLE3_BF16, hidden=512, n_heads=4, n_kv_heads=2, head_dim=128, intermediate=1024)
         kw.update(bad)
         c = _cfg(**kw)

@@ -1,7 +1,8 @@
 /*
  * eagle3.h — C ABI of the MI355X (gfx950) library for one EAGLE-3 speculative-decoding step
  * (arXiv 2503.01840): multi-layer feature fusion, draft-tree expansion, tree-masked verification
- * and the acceptance walk.
+ * and the acceptance walk, plus what closes the loop around a step (prefill, commit, batched chain
+ * drafting) and the training-time-test attention forward.
  *
  * General conventions
  *   - Unless marked HOST, every tensor pointer is a DEVICE pointer allocated and owned by the caller.
@@ -11,7 +12,7 @@
  *     (y = W x).  Weights, norm gains, the embedding table and KV caches have the storage type
  *     `eagle3_config.dtype` (bf16 or fp32); activations exchanged across this boundary (features,
  *     logits, scores, uniforms) are fp32; indices are int32.
- *   - The four step calls enqueue kernels on the given stream and return without synchronising.
+ *   - Every call outside the life-cycle section enqueues kernels on the given stream and returns without synchronising.
  *     Two calls using the same context must not overlap in time (they share the workspace).
  *   - Return value: EAGLE3_OK or a negative error code; nothing is enqueued when an argument check
  *     fails.  Device-side contents (e.g. parent[i] < i, token ids inside the vocabulary) are NOT

@@ -192,3 +192,15 @@ def test_draft_expand_sweep(shape):
             assert np.array_equal(got[key], ref[key]), (case, key)
         assert np.max(np.abs(got["score"] - ref["score"])) < tol, case
         assert all(got["parent"][j] < j for j in range(1, N)) and got["parent"][0] == -1, case
+
+
+def test_chain_drafting_sweep():
+    """8 random batched chain drafts on the exact fp32 model (batch 1..12, 1..6 new rows per sequence with ragged
+    counts, chains of 1..4 tokens, ragged draft contexts of 0..89 tokens): tokens, cumulative log-probabilities and
+    the cache rows against the per-sequence oracle."""
+    from test_gpu_decode import _chain_case
+    E = _E()
+    rs = np.random.RandomState(15 + 100 * SALT)
+    for i in range(8):
+        B, rows1, L = int(rs.randint(1, 13)), int(rs.randint(1, 7)), int(rs.randint(1, 5))
+        _chain_case(E, S.get_shape("c1"), B, rows1, L, 200 + 10 * SALT + i, 1e-4)

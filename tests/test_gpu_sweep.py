@@ -204,3 +204,22 @@ def test_chain_drafting_sweep():
     for i in range(8):
         B, rows1, L = int(rs.randint(1, 13)), int(rs.randint(1, 7)), int(rs.randint(1, 5))
         _chain_case(E, S.get_shape("c1"), B, rows1, L, 200 + 10 * SALT + i, 1e-4)
+
+
+def test_ttt_attention_sweep():
+    """10 random training-time-test attention shapes (1..400 positions, grouped heads, simulated steps 0..4) in bf16
+    storage, and 4 in fp32, every output element against the oracle's dense-mask form."""
+    import torch
+    from test_gpu_ttt import _case
+    E = _E()
+    rs = np.random.RandomState(16 + 100 * SALT)
+    for i in range(10):
+        T = int(rs.choice([1, 31, 32, 33, 63, 64, 65, 127, 128, 129])) if rs.rand() < 0.5 else int(rs.randint(1, 401))
+        H, Hkv = [(2, 1), (4, 2), (4, 4), (8, 2), (2, 2)][int(rs.randint(5))]
+        s = int(rs.randint(0, 5))
+        err = _case(E, T, H, Hkv, 128, s, torch.bfloat16, 300 + 20 * SALT + i)
+        assert err < 2e-3, (T, H, Hkv, s, err)
+    for i in range(4):
+        T, s = int(rs.randint(1, 120)), int(rs.randint(0, 4))
+        H, Hkv = [(2, 1), (4, 2), (4, 4)][int(rs.randint(3))]
+        assert _case(E, T, H, Hkv, 64, s, torch.float32, 340 + 20 * SALT + i) < 1e-5, (T, H, Hkv, s)

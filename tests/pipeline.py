@@ -79,8 +79,9 @@ def real_prefill_inputs(shape, model, seed=S.SEED):
     dw, emb = model.draft(), model.globals()["embed"]
     g_all = O.fuse_features(dw["w_fc"], pre["taps"][0], pre["taps"][1], pre["taps"][2])
     Kd = np.zeros((P - 1, shape.n_kv_heads, shape.head_dim)); Vd = np.zeros_like(Kd)
-    O.draft_forward(shape, dw, emb, g_all[:P - 1], toks[1:], np.arange(P - 1), Kd, Vd, 0, 0,
-                    np.tril(np.ones((P - 1, P - 1), dtype=bool)), lambda a: a)
+    if P > 1:                                            # a one-token prompt has no position whose next token is known
+        O.draft_forward(shape, dw, emb, g_all[:P - 1], toks[1:], np.arange(P - 1), Kd, Vd, 0, 0,
+                        np.tril(np.ones((P - 1, P - 1), dtype=bool)), lambda a: a)
     root = int(np.argmax(pre["logits"][-1]))
     return {
         "P": P, "n_new": 1, "prefix_tok": toks, "prefill": pre,

@@ -223,3 +223,40 @@ def test_ttt_attention_sweep():
         T, s = int(rs.randint(1, 120)), int(rs.randint(0, 4))
         H, Hkv = [(2, 1), (4, 2), (4, 4)][int(rs.randint(3))]
         assert _case(E, T, H, Hkv, 64, s, torch.float32, 340 + 20 * SALT + i) < 1e-5, (T, H, Hkv, s)
+
+
+def test_prefill_sweep():
+    """6 random prompts (1..90 tokens) prefilled in chunks of 1..64 positions on the exact fp32 model: the target cache
+    of every layer, the draft cache, the last position's logits and fused feature against the oracle's prefill."""
+    E = _E()
+    rs = np.random.RandomState(17 + 100 * SALT)
+    base = S.get_shape("c1")
+    model = PL.OracleModel(base)
+    W = PL.device_weights(base, device=DEV)
+    for i in range(6):
+        T = int(rs.choice([1, 2, 63, 64, 65])) if rs.rand() < 0.4 else int(rs.randint(1, 91))
+        chunk = int(rs.choice([1, 7, 16, 33, 64]))
+        shape = base.with_(prefix_lo=T, prefix_hi=T)
+        inp = PL.real_prefill_inputs(shape, model, seed=S.SEED + 400 + 10 * SALT + i)
+        prompt, pre = inp["prefix_tok"], inp["prefill"]
+        ctx = E.Eagle3Context(shape, max_batch=1, max_nodes=chunk, max_depth=2, max_topk=2, max_new=chunk, device=DEV)
+        ctx.set_weights(W["target"], W["draft"])
+        cap = T + 8
+        z = lambda: torch.zeros(cap, shape.n_kv_heads, shape.head_dim, dtype=torch.float32, device=DEV)
+        ks, vs = [z() for _ in range(shape.n_layers)], [z() for _ in range(shape.n_layers)]
+        i32 = lambda v: torch.tensor(v, dtype=torch.int32, device=DEV)
+        kv = E.KVCache(ks, vs, i32([0, cap]), i32([0]), 0)
+        dkv = E.KVCache([z()], [z()], i32([0, cap]), i32([0]), 0)
+        g_last, logits = E.eagle3_prefill(ctx, torch.as_tensor(prompt, dtype=torch.int32, device=DEV), kv, dkv)
+        torch.cuda.synchronize()
+        case = (i, T, chunk)
+        assert int(kv.prefix_len[0]) == T and int(dkv.prefix_len[0]) == T - 1, case
+        for l in range(shape.n_layers):
+            assert np.max(np.abs(ks[l][:T].cpu().numpy() - pre["k_new"][l])) < 1e-4, case
+            assert np.max(np.abs(vs[l][:T].cpu().numpy() - pre["v_new"][l])) < 1e-4, case
+        assert np.max(np.abs(logits.cpu().numpy() - pre["logits"][-1])) < 1e-4, case
+        assert np.max(np.abs(g_last.cpu().numpy() - inp["g_new"][0].numpy())) < 1e-4, case
+        if T > 1:
+            Kd, Vd = inp["draft_kv"]
+            assert np.max(np.abs(dkv.k_layers[0][:T - 1].cpu().numpy() - Kd.numpy())) < 1e-4, case
+            assert np.max(np.abs(dkv.v_layers[0][:T - 1].cpu().numpy() - Vd.numpy())) < 1e-4, case

@@ -260,3 +260,41 @@ def test_prefill_sweep():
             Kd, Vd = inp["draft_kv"]
             assert np.max(np.abs(dkv.k_layers[0][:T - 1].cpu().numpy() - Kd.numpy())) < 1e-4, case
             assert np.max(np.abs(dkv.v_layers[0][:T - 1].cpu().numpy() - Vd.numpy())) < 1e-4, case
+
+
+def test_multi_step_decode_sweep():
+    """4 random prompts (2..40 tokens) taken through eagle3_prefill and 8 draft-verify-commit cycles with random
+    planted acceptance lengths and random tree sizes, entirely on the library's own state: the emitted tokens must be
+    the oracle target's plain greedy decoding."""
+    from test_gpu_decode import gpu_decode
+    from test_oracle_decode import planted_hook
+    E = _E()
+    rs = np.random.RandomState(18 + 100 * SALT)
+    shape = S.get_shape("c1")
+    D, K = shape.depth, shape.topk
+    model = PL.OracleModel(shape)
+    W = PL.device_weights(shape, device=DEV)
+    n_steps = 8
+    for i in range(4):
+        T = int(rs.randint(2, 41))
+        N = int(rs.randint(D + 2, 31))
+        prompt = S.uniform_ints(S.SEED + 500 + 10 * SALT + i, S.TensorIds.PREFIX_TOK, (T,), 0, shape.vocab).numpy()
+        ref = O.greedy_decode(shape, model.layer, model.globals(), prompt, n_steps * (D + 1) + 2)
+        ctx = E.Eagle3Context(shape, max_batch=1, max_nodes=32, max_depth=D, max_topk=K, max_new=32, device=DEV)
+        ctx.set_weights(W["target"], W["draft"])
+        cap = T + n_steps * (D + 1) + N + (D - 1) * K + 8
+        z = lambda: torch.zeros(cap, shape.n_kv_heads, shape.head_dim, dtype=torch.float32, device=DEV)
+        i32 = lambda v: torch.tensor(v, dtype=torch.int32, device=DEV)
+        kv = E.KVCache([z() for _ in range(shape.n_layers)], [z() for _ in range(shape.n_layers)], i32([0, cap]), i32([0]), 0)
+        dkv = E.KVCache([z()], [z()], i32([0, cap]), i32([0]), 0)
+        g_last, logits = E.eagle3_prefill(ctx, torch.as_tensor(prompt, dtype=torch.int32, device=DEV), kv, dkv)
+        root = int(torch.argmax(logits))
+        assert root == ref[0], (i, T)
+        kv.set_max_prefix_len(T)
+        dkv.set_max_prefix_len(T - 1)
+        wanted = [int(x) for x in rs.randint(0, D + 1, size=n_steps)]
+        state = {"kv": kv, "dkv": dkv, "g_new": g_last[None].contiguous(), "tok_new": i32([root]), "P": T, "Pd": T - 1}
+        emitted, accept_lens, trees = gpu_decode(E, ctx, shape, state, n_steps, D, K, N, planted_hook(ref, wanted))
+        assert emitted == ref[:len(emitted)], (i, T, N, wanted, accept_lens)
+        reach = [int(O.tree_depth(pp).max()) for _, pp, _ in trees]      # a small tree may be shallower than the plant
+        assert all(a >= min(w, r) for a, w, r in zip(accept_lens, wanted, reach)), (wanted, reach, accept_lens)

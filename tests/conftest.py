@@ -25,3 +25,16 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(autouse=True)
+def _release_device_memory(request):
+    """The full-size cases hold up to ~150 GB of synthetic weights: hand the cached blocks back after every GPU test so
+    that the next one never depends on what the allocator still holds."""
+    yield
+    if "gpu" in request.keywords:
+        import gc
+        import torch
+        gc.collect()
+        if torch.cuda.is_available():
+            torch.cuda.empty_cache()

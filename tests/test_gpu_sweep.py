@@ -298,3 +298,60 @@ def test_multi_step_decode_sweep():
         assert emitted == ref[:len(emitted)], (i, T, N, wanted, accept_lens)
         reach = [int(O.tree_depth(pp).max()) for _, pp, _ in trees]      # a small tree may be shallower than the plant
         assert all(a >= min(w, r) for a, w, r in zip(accept_lens, wanted, reach)), (wanted, reach, accept_lens)
+
+
+@pytest.mark.parametrize("hidden,inter", [(1024, 1408), (1152, 2816), (1280, 1536), (1408, 1664)])
+def test_gemm_stage_count_sweep(hidden, inter):
+    """bf16 models whose projections have 8, 9, 10 and 11 (hidden) and 11, 22, 12 and 13 (intermediate) K stages: every
+    remainder of the GEMM kernels' unrolled stage loops and of their split-K choices, through one verification
+    (17, 60 rows: the few-row and the 64-row kernels; 96 rows in a batch: the many-row kernel) and one draft expansion."""
+    E = _E()
+    shape = S.get_shape("c2").with_(name=f"h{hidden}", hidden=hidden, n_heads=hidden // 128, n_kv_heads=2 if hidden % 256 == 0 else 1,
+                                    intermediate=inter, vocab=2048 + 64, draft_vocab=1024, n_layers=1, taps=(0, 0, 0),
+                                    prefix_lo=70, prefix_hi=70, depth=3, topk=4, n_nodes=17)
+    model = PL.OracleModel(shape)
+    ctx = _ctx(shape, max_batch=6, max_nodes=64)
+    rs = np.random.RandomState(hidden + 100 * SALT)
+    for N in (17, 60):
+        parent = S.random_tree(S.SEED, 800 + N, N, 6, 8)[0]
+        P = int(rs.randint(1, 200))
+        toks = S.uniform_ints(S.SEED + N, S.TensorIds.TREE_TOK, (N,), 0, shape.vocab).numpy()
+        pairs = [S.kv_layer(shape, 0, P, seed=S.SEED + N)]
+        ref = O.tree_verify(shape, model.layer, model.globals(), toks, parent, lambda l: tuple(O.as_f64(t) for t in pairs[l]),
+                            rounding="bf16")
+        ks, vs, indptr, plen, _ = PL.device_kv(pairs, N, DEV)
+        logits, taps = E.eagle3_tree_verify(ctx, torch.as_tensor(toks, dtype=torch.int32, device=DEV)[None],
+                                            torch.as_tensor(parent, dtype=torch.int32, device=DEV)[None],
+                                            E.KVCache(ks, vs, indptr, plen, P))
+        torch.cuda.synchronize()
+        assert np.max(np.abs(logits[0].cpu().numpy() - ref["logits"])) < 2e-2, (hidden, N)
+        assert np.max(np.abs(taps[:, 0].cpu().numpy() - ref["taps"])) < 2e-2 * max(1.0, float(np.sqrt(np.mean(ref["taps"] ** 2)))), (hidden, N)
+    # a batch of 6 x 16 = 96 rows
+    B, N = 6, 16
+    plens = [int(x) for x in rs.randint(0, 150, size=B)]
+    parents = np.stack([S.random_tree(S.SEED, 820 + b, N, 4, 3)[0] for b in range(B)]).astype(np.int32)
+    toks = S.uniform_ints(S.SEED + 7, S.TensorIds.TREE_TOK, (B, N), 0, shape.vocab).numpy()
+    indptr = np.zeros(B + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum(np.array(plens) + N)
+    K_all, V_all = S.kv_layer(shape, 0, int(indptr[-1]))
+    kv = E.KVCache([K_all.to(DEV)], [V_all.to(DEV)], torch.as_tensor(indptr, dtype=torch.int32, device=DEV),
+                   torch.tensor(plens, dtype=torch.int32, device=DEV), max(plens))
+    logits, taps = E.eagle3_tree_verify(ctx, torch.as_tensor(toks, dtype=torch.int32, device=DEV),
+                                        torch.as_tensor(parents, dtype=torch.int32, device=DEV), kv)
+    torch.cuda.synchronize()
+    for b in range(B):
+        base, P = int(indptr[b]), plens[b]
+        ref = O.tree_verify(shape, model.layer, model.globals(), toks[b], parents[b],
+                            lambda l: tuple(O.as_f64(t) for t in S.kv_layer(shape, l, P, first_slot=base)), rounding="bf16")
+        assert np.max(np.abs(logits[b].cpu().numpy() - ref["logits"])) < 2e-2, (hidden, "batch", b)
+    # one draft expansion (2k-wide draft input: twice as many stages)
+    D, K, N = 3, 4, 17
+    inp = PL.synthetic_step_inputs(shape, n_new=2, prefix=72)
+    ks, vs, indptr, plen, P = PL.device_kv([inp["draft_kv"]], 2 + (D - 1) * K, DEV)
+    got = E.eagle3_draft_expand(ctx, inp["g_new"].to(DEV), inp["tok_new"].to(DEV), E.KVCache(ks, vs, indptr, plen, P), D, K, N, debug=True)
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in got.items()}
+    ref = PL.oracle_draft(shape, model, inp, D, K, N, follow={"pool_tok": got["pool_tok"], "frontier": got["frontier"], "chosen": got["chosen"]})
+    for key in ("tree_tok", "parent", "depth", "chosen"):
+        assert np.array_equal(got[key], ref[key]), (hidden, key)
+    assert np.max(np.abs(got["score"] - ref["score"])) < 2e-2, hidden
